@@ -1,0 +1,137 @@
+/*
+ * stl.h -- C ABI of the Strassen-Tile (STL) operator library for AMD MI355X (gfx950).
+ *
+ * The operator (paper: Definition 3.1, Eq. (2)) replaces C = X*W by
+ *
+ *     vec(C_{I,J}) = D^T ( sum_L (E_X vec X_{I,L}) (.) What[:,L,J] ),     t x t tiles,
+ *
+ * evaluated with the three-step plane algorithm (Claim 3.4, Algorithm 1):
+ * (i) encode X tiles into r planes, (ii) r independent plane products on the matrix
+ * cores, (iii) decode every output tile once.  What are the stored encoded weight
+ * planes (Remark "Fake Encoding"): What[p][L][J] = (E_W vec W_{L,J})_p.
+ *
+ * Letters: X is m x k, W is k x n, C is m x n; M=m/t, K=k/t, N=n/t tile counts.
+ *
+ * Conventions for every entry point
+ *  - All matrices are dense, row-major, without strides.  vec() of a tile is
+ *    row-major: vec(T)[a*t+b] = T[a][b].  E_X, E_W, D are r x t^2 row-major
+ *    (Definition 3.1); the decoder is applied as D^T.
+ *  - Plane tensors (What, Xhat, Yhat, dWhat) are plane-major: [p][row tile][col tile].
+ *  - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned.
+ *    The library allocates and frees no device memory: scratch comes from `ws`
+ *    (size from stl_workspace_bytes).  Outputs must not alias inputs or `ws`.
+ *  - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream); they never synchronise and keep no state between calls.
+ *  - Every argument is validated before any launch.  Nothing is launched when a
+ *    non-STL_OK status is returned for an argument error.  Supported: t == 4,
+ *    1 <= r <= 64, m, k, n positive multiples of t, dtype in {F32, BF16}.
+ *  - dtype selects the storage type of X, W, What, E_X, E_W, D, C, dC, dX, Xhat,
+ *    Yhat.  Arithmetic: fp32 multiply-add throughout for F32; for BF16 the plane
+ *    products are bf16 x bf16 -> fp32 on MFMA, encode/decode are fp32, and each
+ *    stored intermediate (Xhat, Yhat when it leaves registers, dYhat, dXhat) and
+ *    each output is rounded to bf16 once (round-to-nearest-even).
+ *    dWhat, dE_X, dD are always fp32.
+ *  - No exception or abort crosses this boundary.
+ */
+#ifndef STL_H_
+#define STL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    STL_OK = 0,
+    STL_ERR_INVALID_ARG = 1,   /* null pointer, non-positive or non-divisible size, r out of range */
+    STL_ERR_UNSUPPORTED = 2,   /* t != 4, unknown dtype or flag */
+    STL_ERR_WORKSPACE = 3,     /* ws is NULL or ws_bytes too small */
+    STL_ERR_HIP = 4            /* a HIP call failed; text in stl_last_error() */
+} stl_status_t;
+
+typedef enum { STL_F32 = 0, STL_BF16 = 1 } stl_dtype_t;
+
+typedef struct {
+    int64_t m, k, n;   /* X is m x k, What encodes a k x n weight, C is m x n */
+    int32_t t, r;      /* tile size (4) and tensor rank (number of planes) */
+    int32_t dtype;     /* stl_dtype_t */
+} stl_problem_t;
+
+/* which operation a workspace is sized for */
+enum { STL_OP_ENCODE_WEIGHT = 0, STL_OP_FORWARD = 1, STL_OP_BACKWARD = 2 };
+
+/* forward variants (low byte of `flags`) and modifiers */
+enum {
+    STL_FLAG_AUTO = 0,      /* library picks the fastest variant for the shape */
+    STL_FLAG_UNFUSED = 1,   /* Algorithm 1 as three launches: encode -> plane products -> decode   */
+    STL_FLAG_EPILOGUE = 2,  /* encode launch, then plane products with D applied in the epilogue   */
+    STL_FLAG_FUSED = 3,     /* one launch: encode -> MFMA -> decode, no plane ever written to HBM   */
+    STL_FLAG_VARIANT_MASK = 0xff,
+    STL_FLAG_GELU = 0x100   /* C <- gelu(C) (exact erf form) applied in fp32 before the final rounding */
+};
+
+/* Bytes of device scratch `ws` needed by op (STL_OP_*) with `flags`; 0 on invalid problem. */
+size_t stl_workspace_bytes(const stl_problem_t *prob, int op, int flags);
+
+/*
+ * W-encoding (plane definition before Claim 3.4; Remark "Fake Encoding"):
+ *   What[p][L][J] = sum_q E_W[p][q] * vec(W_{L,J})[q].
+ * W: k x n (in).  E_W: r x 16 (in).  What: r x K x N (out).  Set-up cost, off the hot path.
+ */
+stl_status_t stl_encode_weight(const stl_problem_t *prob, const void *W, const void *E_W,
+                               void *What, void *stream);
+
+/*
+ * Forward C = X <> W (Definition 3.1 / Eq. (2); Algorithm 1).
+ * X: m x k (in).  What: r x K x N (in).  E_X, D: r x 16 (in).  C: m x n (out).
+ * Yhat_save: NULL, or r x M x N (out, storage dtype): the encoded output
+ *   Yhat[p] = Xhat[p] * What[p] (Claim 3.4) is also written there, for stl_backward.
+ * ws / ws_bytes: scratch of at least stl_workspace_bytes(prob, STL_OP_FORWARD, flags).
+ */
+stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *What,
+                         const void *E_X, const void *D, void *C, void *Yhat_save,
+                         void *ws, size_t ws_bytes, int flags, void *stream);
+
+/*
+ * Backward of the scalar <dC, C> (chain rule through Algorithm 1's three linear steps;
+ * the paper states only that these gradients exist, Section "Strassen-Tile Operator"):
+ *   dYhat[p][I][J] = sum_q D[p][q] dc[I][J][q]          dD[p][q]   = sum_{I,J} Yhat[p][I][J] dc[I][J][q]
+ *   dXhat[p] = dYhat[p] * What[p]^T                     dWhat[p]   = Xhat[p]^T * dYhat[p]
+ *   dx[I][L][q] = sum_p E_X[p][q] dXhat[p][I][L]        dE_X[p][q] = sum_{I,L} dXhat[p][I][L] x[I][L][q]
+ * dC: m x n (in).  Yhat_saved: NULL (Yhat is recomputed) or what stl_forward wrote to Yhat_save.
+ * dX: m x k (out, storage dtype).  dWhat: r x K x N, dE_X, dD: r x 16 (out, fp32).
+ * Any of the four outputs may be NULL to skip it.
+ * accumulate: 0 overwrites dWhat/dE_X/dD; 1 adds into them (fp32 gradient accumulation).
+ * Results are bitwise reproducible run to run (no floating-point atomics).
+ */
+stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *What,
+                          const void *E_X, const void *D, const void *dC, const void *Yhat_saved,
+                          void *dX, float *dWhat, float *dE_X, float *dD, int accumulate,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The three steps of Algorithm 1 on their own (for measurement and stage-level tests).
+ *   stl_encode_activation: Xhat[p][I][L] = (E_X vec X_{I,L})_p        X m x k -> Xhat r x M x K
+ *   stl_plane_matmul:      Yhat[p] = Xhat[p] * What[p]  (Claim 3.4)    -> Yhat r x M x N
+ *   stl_decode:            vec(C_{I,J}) = D^T Yhat[:,I,J]              -> C m x n   (flags: STL_FLAG_GELU or 0)
+ */
+stl_status_t stl_encode_activation(const stl_problem_t *prob, const void *X, const void *E_X,
+                                   void *Xhat, void *stream);
+stl_status_t stl_plane_matmul(const stl_problem_t *prob, const void *Xhat, const void *What,
+                              void *Yhat, void *stream);
+stl_status_t stl_decode(const stl_problem_t *prob, const void *Yhat, const void *D, void *C,
+                        int flags, void *stream);
+
+/* Static text for a status code. */
+const char *stl_status_string(stl_status_t status);
+/* Text of the last error raised on the calling thread ("" if none).  Thread-local storage. */
+const char *stl_last_error(void);
+/* Library version, e.g. "0.1.0 gfx950". */
+const char *stl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STL_H_ */

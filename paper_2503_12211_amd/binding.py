@@ -1,0 +1,157 @@
+"""ctypes binding with the same names as the entry points declared in include/stl.h.
+
+Argument marshalling only: device tensors (anything with ``data_ptr()``) or raw integer
+addresses go in, the status code is checked, nothing is computed here.
+"""
+from __future__ import annotations
+
+import ctypes
+from dataclasses import dataclass
+from pathlib import Path
+
+_HERE = Path(__file__).resolve().parent
+_LIB_PATH = _HERE / "libstl_mi355x.so"
+
+STL_F32, STL_BF16 = 0, 1
+STL_OP_ENCODE_WEIGHT, STL_OP_FORWARD, STL_OP_BACKWARD = 0, 1, 2
+STL_FLAG_AUTO, STL_FLAG_UNFUSED, STL_FLAG_EPILOGUE, STL_FLAG_FUSED = 0, 1, 2, 3
+STL_FLAG_GELU = 0x100
+
+# every symbol include/stl.h declares
+SYMBOLS = (
+    "stl_workspace_bytes", "stl_encode_weight", "stl_forward", "stl_backward", "stl_encode_activation",
+    "stl_plane_matmul", "stl_decode", "stl_status_string", "stl_last_error", "stl_version",
+)
+
+
+class StlError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"STL status {status}: {message}")
+        self.status = status
+
+
+class _CProblem(ctypes.Structure):
+    _fields_ = [("m", ctypes.c_int64), ("k", ctypes.c_int64), ("n", ctypes.c_int64),
+                ("t", ctypes.c_int32), ("r", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+@dataclass(frozen=True)
+class Problem:
+    m: int
+    k: int
+    n: int
+    r: int
+    dtype: int = STL_BF16
+    t: int = 4
+
+    def c(self) -> _CProblem:
+        return _CProblem(self.m, self.k, self.n, self.t, self.r, self.dtype)
+
+
+_lib = None
+_P = ctypes.c_void_p
+
+
+def library_path() -> Path:
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not _LIB_PATH.exists():
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2503_12211_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(str(_LIB_PATH))
+    pp = ctypes.POINTER(_CProblem)
+    lib.stl_workspace_bytes.restype = ctypes.c_size_t
+    lib.stl_workspace_bytes.argtypes = [pp, ctypes.c_int, ctypes.c_int]
+    lib.stl_encode_weight.argtypes = [pp, _P, _P, _P, _P]
+    lib.stl_forward.argtypes = [pp, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, ctypes.c_int, _P]
+    lib.stl_backward.argtypes = [pp, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_int, _P, ctypes.c_size_t, _P]
+    lib.stl_encode_activation.argtypes = [pp, _P, _P, _P, _P]
+    lib.stl_plane_matmul.argtypes = [pp, _P, _P, _P, _P]
+    lib.stl_decode.argtypes = [pp, _P, _P, _P, ctypes.c_int, _P]
+    for name in ("stl_encode_weight", "stl_forward", "stl_backward", "stl_encode_activation", "stl_plane_matmul",
+                 "stl_decode"):
+        getattr(lib, name).restype = ctypes.c_int
+    lib.stl_status_string.restype = ctypes.c_char_p
+    lib.stl_status_string.argtypes = [ctypes.c_int]
+    lib.stl_last_error.restype = ctypes.c_char_p
+    lib.stl_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def exported_symbols():
+    """Names from include/stl.h that the built library exports."""
+    lib = _load()
+    return [s for s in SYMBOLS if hasattr(lib, s)]
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(status: int):
+    if status != 0:
+        raise StlError(status, stl_last_error() or stl_status_string(status))
+
+
+def stl_status_string(status: int) -> str:
+    return _load().stl_status_string(status).decode()
+
+
+def stl_last_error() -> str:
+    return _load().stl_last_error().decode()
+
+
+def stl_version() -> str:
+    return _load().stl_version().decode()
+
+
+def stl_workspace_bytes(prob: Problem, op: int, flags: int = 0) -> int:
+    return int(_load().stl_workspace_bytes(ctypes.byref(prob.c()), op, flags))
+
+
+def stl_encode_weight(prob: Problem, W, E_W, What, stream=None) -> None:
+    _check(_load().stl_encode_weight(ctypes.byref(prob.c()), _ptr(W), _ptr(E_W), _ptr(What), _stream(stream)))
+
+
+def stl_forward(prob: Problem, X, What, E_X, D, C, Yhat_save=None, ws=None, ws_bytes: int = 0,
+                flags: int = STL_FLAG_AUTO, stream=None) -> None:
+    _check(_load().stl_forward(ctypes.byref(prob.c()), _ptr(X), _ptr(What), _ptr(E_X), _ptr(D), _ptr(C),
+                               _ptr(Yhat_save), _ptr(ws), ws_bytes, flags, _stream(stream)))
+
+
+def stl_backward(prob: Problem, X, What, E_X, D, dC, Yhat_saved, dX, dWhat, dE_X, dD, accumulate: int = 0,
+                 ws=None, ws_bytes: int = 0, stream=None) -> None:
+    _check(_load().stl_backward(ctypes.byref(prob.c()), _ptr(X), _ptr(What), _ptr(E_X), _ptr(D), _ptr(dC),
+                                _ptr(Yhat_saved), _ptr(dX), _ptr(dWhat), _ptr(dE_X), _ptr(dD), accumulate,
+                                _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def stl_encode_activation(prob: Problem, X, E_X, Xhat, stream=None) -> None:
+    _check(_load().stl_encode_activation(ctypes.byref(prob.c()), _ptr(X), _ptr(E_X), _ptr(Xhat), _stream(stream)))
+
+
+def stl_plane_matmul(prob: Problem, Xhat, What, Yhat, stream=None) -> None:
+    _check(_load().stl_plane_matmul(ctypes.byref(prob.c()), _ptr(Xhat), _ptr(What), _ptr(Yhat), _stream(stream)))
+
+
+def stl_decode(prob: Problem, Yhat, D, C, flags: int = 0, stream=None) -> None:
+    _check(_load().stl_decode(ctypes.byref(prob.c()), _ptr(Yhat), _ptr(D), _ptr(C), flags, _stream(stream)))

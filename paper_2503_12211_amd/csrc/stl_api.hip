@@ -1,0 +1,274 @@
+// C ABI of the STL library: argument validation, workspace carving and launch sequencing.
+// Every step of the operator runs in the kernels of this library; there is no host fallback.
+#include "../../include/stl.h"
+#include "stl_kernels.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+stl_status_t fail(stl_status_t st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+stl_status_t hip_fail(hipError_t e, const char *what)
+{
+    return fail(STL_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+struct Dims {
+    int M, K, N, r;
+    size_t es;  // element size of the storage dtype
+};
+
+constexpr int64_t kMaxDim = (int64_t)1 << 24;  // per-dimension cap; keeps tile indices in int
+
+stl_status_t check_problem(const stl_problem_t *p, Dims *d)
+{
+    if (!p) return fail(STL_ERR_INVALID_ARG, "problem descriptor is NULL");
+    if (p->dtype != STL_F32 && p->dtype != STL_BF16) return fail(STL_ERR_UNSUPPORTED, "unknown dtype %d", p->dtype);
+    if (p->t != 4) return fail(STL_ERR_UNSUPPORTED, "tile size t=%d is not supported (t must be 4)", p->t);
+    if (p->r < 1 || p->r > 64) return fail(STL_ERR_INVALID_ARG, "tensor rank r=%d outside [1,64]", p->r);
+    if (p->m < 4 || p->k < 4 || p->n < 4) return fail(STL_ERR_INVALID_ARG, "m, k, n must be positive");
+    if (p->m % 4 || p->k % 4 || p->n % 4)
+        return fail(STL_ERR_INVALID_ARG, "m=%lld k=%lld n=%lld must be multiples of t=4", (long long)p->m,
+                    (long long)p->k, (long long)p->n);
+    if (p->m > kMaxDim || p->k > kMaxDim || p->n > kMaxDim)
+        return fail(STL_ERR_INVALID_ARG, "dimension larger than %lld", (long long)kMaxDim);
+    d->M = (int)(p->m / 4);
+    d->K = (int)(p->k / 4);
+    d->N = (int)(p->n / 4);
+    d->r = p->r;
+    d->es = p->dtype == STL_F32 ? 4 : 2;
+    // plane tensors are indexed with size_t, but keep each below 2^40 elements as a sanity bound
+    const double big = 1099511627776.0;
+    if ((double)d->r * d->M * d->K > big || (double)d->r * d->M * d->N > big || (double)d->r * d->K * d->N > big)
+        return fail(STL_ERR_INVALID_ARG, "plane tensors too large");
+    return STL_OK;
+}
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct FwdWs {
+    size_t xhat, yhat, total;
+};
+
+int variant_of(int flags) { return flags & STL_FLAG_VARIANT_MASK; }
+
+stl_status_t check_flags(int flags, int *variant)
+{
+    if (flags & ~(STL_FLAG_VARIANT_MASK | STL_FLAG_GELU)) return fail(STL_ERR_UNSUPPORTED, "unknown flag bits 0x%x", flags);
+    int v = variant_of(flags);
+    if (v > STL_FLAG_FUSED) return fail(STL_ERR_UNSUPPORTED, "unknown forward variant %d", v);
+    *variant = v;
+    return STL_OK;
+}
+
+FwdWs fwd_layout(const Dims &d, int variant)
+{
+    FwdWs w{};
+    size_t off = 0;
+    (void)variant;
+    w.xhat = off;
+    off += align256((size_t)d.r * d.M * d.K * d.es);
+    w.yhat = off;
+    off += align256((size_t)d.r * d.M * d.N * d.es);
+    w.total = off;
+    return w;
+}
+
+struct BwdWs {
+    size_t xhat, dyhat, dxhat, yhat, part, total;
+};
+
+BwdWs bwd_layout(const Dims &d)
+{
+    BwdWs w{};
+    size_t off = 0;
+    const size_t pk = align256((size_t)d.r * d.M * d.K * d.es), pn = align256((size_t)d.r * d.M * d.N * d.es);
+    w.xhat = off;
+    off += pk;
+    w.dyhat = off;
+    off += pn;
+    w.dxhat = off;
+    off += pk;
+    w.yhat = off;
+    off += pn;
+    const int nb_n = stl::outer_reduce_blocks((int64_t)d.M * d.N), nb_k = stl::outer_reduce_blocks((int64_t)d.M * d.K);
+    w.part = off;
+    off += align256((size_t)(nb_n > nb_k ? nb_n : nb_k) * d.r * 16 * sizeof(float));
+    w.total = off;
+    return w;
+}
+
+#define STL_HIP(call, what)                                \
+    do {                                                   \
+        hipError_t e__ = (call);                           \
+        if (e__ != hipSuccess) return hip_fail(e__, what); \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char *stl_status_string(stl_status_t s)
+{
+    switch (s) {
+        case STL_OK: return "ok";
+        case STL_ERR_INVALID_ARG: return "invalid argument";
+        case STL_ERR_UNSUPPORTED: return "unsupported";
+        case STL_ERR_WORKSPACE: return "workspace missing or too small";
+        case STL_ERR_HIP: return "HIP error";
+    }
+    return "unknown status";
+}
+
+const char *stl_last_error(void) { return g_err; }
+
+const char *stl_version(void) { return "0.1.0 gfx950"; }
+
+size_t stl_workspace_bytes(const stl_problem_t *prob, int op, int flags)
+{
+    Dims d;
+    if (check_problem(prob, &d) != STL_OK) return 0;
+    switch (op) {
+        case STL_OP_ENCODE_WEIGHT: return 0;
+        case STL_OP_FORWARD: {
+            int v;
+            if (check_flags(flags, &v) != STL_OK) return 0;
+            return fwd_layout(d, v).total;
+        }
+        case STL_OP_BACKWARD: return bwd_layout(d).total;
+    }
+    fail(STL_ERR_INVALID_ARG, "unknown op %d", op);
+    return 0;
+}
+
+stl_status_t stl_encode_weight(const stl_problem_t *prob, const void *W, const void *E_W, void *What, void *stream)
+{
+    Dims d;
+    stl_status_t st = check_problem(prob, &d);
+    if (st != STL_OK) return st;
+    if (!W || !E_W || !What) return fail(STL_ERR_INVALID_ARG, "stl_encode_weight: NULL pointer");
+    STL_HIP(stl::launch_encode(prob->dtype, W, E_W, What, d.K, d.N, d.r, (hipStream_t)stream), "encode_weight");
+    return STL_OK;
+}
+
+stl_status_t stl_encode_activation(const stl_problem_t *prob, const void *X, const void *E_X, void *Xhat, void *stream)
+{
+    Dims d;
+    stl_status_t st = check_problem(prob, &d);
+    if (st != STL_OK) return st;
+    if (!X || !E_X || !Xhat) return fail(STL_ERR_INVALID_ARG, "stl_encode_activation: NULL pointer");
+    STL_HIP(stl::launch_encode(prob->dtype, X, E_X, Xhat, d.M, d.K, d.r, (hipStream_t)stream), "encode_activation");
+    return STL_OK;
+}
+
+stl_status_t stl_plane_matmul(const stl_problem_t *prob, const void *Xhat, const void *What, void *Yhat, void *stream)
+{
+    Dims d;
+    stl_status_t st = check_problem(prob, &d);
+    if (st != STL_OK) return st;
+    if (!Xhat || !What || !Yhat) return fail(STL_ERR_INVALID_ARG, "stl_plane_matmul: NULL pointer");
+    stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false};
+    STL_HIP(stl::launch_plane_gemm(prob->dtype, g, Xhat, What, Yhat, (hipStream_t)stream), "plane_matmul");
+    return STL_OK;
+}
+
+stl_status_t stl_decode(const stl_problem_t *prob, const void *Yhat, const void *D, void *C, int flags, void *stream)
+{
+    Dims d;
+    stl_status_t st = check_problem(prob, &d);
+    if (st != STL_OK) return st;
+    if (!Yhat || !D || !C) return fail(STL_ERR_INVALID_ARG, "stl_decode: NULL pointer");
+    if (flags & ~STL_FLAG_GELU) return fail(STL_ERR_UNSUPPORTED, "stl_decode: unknown flag bits 0x%x", flags);
+    STL_HIP(stl::launch_decode(prob->dtype, Yhat, D, C, d.M, d.N, d.r, (flags & STL_FLAG_GELU) != 0, (hipStream_t)stream),
+            "decode");
+    return STL_OK;
+}
+
+stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *What, const void *E_X, const void *D,
+                         void *C, void *Yhat_save, void *ws, size_t ws_bytes, int flags, void *stream)
+{
+    Dims d;
+    stl_status_t st = check_problem(prob, &d);
+    if (st != STL_OK) return st;
+    int variant;
+    st = check_flags(flags, &variant);
+    if (st != STL_OK) return st;
+    if (!X || !What || !E_X || !D || !C) return fail(STL_ERR_INVALID_ARG, "stl_forward: NULL pointer");
+    if (variant == STL_FLAG_EPILOGUE || variant == STL_FLAG_FUSED)
+        return fail(STL_ERR_UNSUPPORTED, "stl_forward: variant %d is not available in this build", variant);
+    const FwdWs w = fwd_layout(d, variant);
+    if (w.total > 0 && (!ws || ws_bytes < w.total))
+        return fail(STL_ERR_WORKSPACE, "stl_forward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
+    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_forward: workspace is not 16-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    const bool gelu = (flags & STL_FLAG_GELU) != 0;
+    char *base = (char *)ws;
+
+    void *xhat = base + w.xhat;
+    void *yhat = Yhat_save ? Yhat_save : (void *)(base + w.yhat);
+    STL_HIP(stl::launch_encode(prob->dtype, X, E_X, xhat, d.M, d.K, d.r, s), "forward/encode");
+    stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false};
+    STL_HIP(stl::launch_plane_gemm(prob->dtype, g, xhat, What, yhat, s), "forward/plane products");
+    STL_HIP(stl::launch_decode(prob->dtype, yhat, D, C, d.M, d.N, d.r, gelu, s), "forward/decode");
+    return STL_OK;
+}
+
+stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *What, const void *E_X, const void *D,
+                          const void *dC, const void *Yhat_saved, void *dX, float *dWhat, float *dE_X, float *dD,
+                          int accumulate, void *ws, size_t ws_bytes, void *stream)
+{
+    Dims d;
+    stl_status_t st = check_problem(prob, &d);
+    if (st != STL_OK) return st;
+    if (!X || !What || !E_X || !D || !dC) return fail(STL_ERR_INVALID_ARG, "stl_backward: NULL input pointer");
+    if (accumulate != 0 && accumulate != 1) return fail(STL_ERR_INVALID_ARG, "stl_backward: accumulate must be 0 or 1");
+    const BwdWs w = bwd_layout(d);
+    if (!ws || ws_bytes < w.total)
+        return fail(STL_ERR_WORKSPACE, "stl_backward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
+    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_backward: workspace is not 16-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    const int dt = prob->dtype;
+    char *base = (char *)ws;
+    void *xhat = base + w.xhat, *dyhat = base + w.dyhat, *dxhat = base + w.dxhat;
+    float *part = (float *)(base + w.part);
+
+    const bool need_xhat = dWhat || (dD && !Yhat_saved);
+    if (need_xhat) STL_HIP(stl::launch_encode(dt, X, E_X, xhat, d.M, d.K, d.r, s), "backward/encode X");
+    STL_HIP(stl::launch_encode(dt, dC, D, dyhat, d.M, d.N, d.r, s), "backward/encode dC");
+    if (dD) {
+        const void *yhat = Yhat_saved;
+        if (!yhat) {
+            stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false};
+            STL_HIP(stl::launch_plane_gemm(dt, g, xhat, What, base + w.yhat, s), "backward/recompute Yhat");
+            yhat = base + w.yhat;
+        }
+        STL_HIP(stl::launch_outer_reduce(dt, yhat, dC, dD, part, d.M, d.N, d.r, accumulate, s), "backward/dD");
+    }
+    if (dX || dE_X) {
+        // dXhat[p] = dYhat[p] * What[p]^T : contraction over J, What[p] is stored [L][J]
+        stl::GemmDesc g{d.M, d.K, d.N, d.r, false, false, false, false};
+        STL_HIP(stl::launch_plane_gemm(dt, g, dyhat, What, dxhat, s), "backward/dXhat");
+    }
+    if (dWhat) {
+        // dWhat[p] = Xhat[p]^T * dYhat[p] : contraction over I, both operands stored [I][.]
+        stl::GemmDesc g{d.K, d.N, d.M, d.r, true, true, true, accumulate != 0};
+        STL_HIP(stl::launch_plane_gemm(dt, g, xhat, dyhat, dWhat, s), "backward/dWhat");
+    }
+    if (dX) STL_HIP(stl::launch_decode(dt, dxhat, E_X, dX, d.M, d.K, d.r, false, s), "backward/decode dX");
+    if (dE_X) STL_HIP(stl::launch_outer_reduce(dt, dxhat, X, dE_X, part, d.M, d.K, d.r, accumulate, s), "backward/dE_X");
+    return STL_OK;
+}
+
+}  // extern "C"

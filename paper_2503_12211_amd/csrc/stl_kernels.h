@@ -1,0 +1,39 @@
+// Internal launcher interface between the C ABI (stl_api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace stl {
+
+// dtype: 0 = fp32 storage, 1 = bf16 storage (matches stl_dtype_t)
+
+// planes P[p][R][Cc] <- encoder E (r x 16) applied to every 4x4 tile of A (4R x 4Cc)
+hipError_t launch_encode(int dtype, const void *A, const void *E, void *P, int R, int Cc, int r, hipStream_t s);
+// matrix Cmat (4R x 4Cc) <- decoder Dm^T (r x 16 stored) applied to planes P[p][R][Cc]
+hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, int R, int Cc, int r, bool gelu,
+                         hipStream_t s);
+
+// G[p][q] (+)= sum_tiles P[p][tile] * tileview(V)[tile][q]; `part` holds outer_reduce_blocks(R*Cc) * r * 16 floats
+enum { OUTER_TILES_PER_BLOCK = 8192 };
+int outer_reduce_blocks(int64_t tiles);
+hipError_t launch_outer_reduce(int dtype, const void *P, const void *V, float *G, float *part, int R, int Cc, int r,
+                               int accumulate, hipStream_t s);
+
+// Batched plane products  Out[p][i][j] (+)= sum_l A[p](i,l) * B[p](l,j),  p < batch, dense planes.
+struct GemmDesc {
+    int Mi, Nj, Kl;   // output rows, output columns, contraction length (all in tiles of the STL problem)
+    int batch;        // number of planes r
+    bool a_kmajor;    // false: A[p] stored [i][l] (l contiguous);  true: stored [l][i] (i contiguous)
+    bool b_kmajor;    // true:  B[p] stored [l][j] (j contiguous);  false: stored [j][l] (l contiguous)
+    bool out_f32;     // output stored as fp32 regardless of dtype (weight gradient)
+    bool accumulate;  // Out += result (only with out_f32)
+};
+hipError_t launch_plane_gemm(int dtype, const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s);
+// the slow any-shape path, also used directly for fp32 storage
+hipError_t launch_plane_gemm_generic(int dtype, const GemmDesc &g, const void *A, const void *B, void *Out,
+                                     hipStream_t s);
+// bf16 MFMA path; returns false in *ok if the shape is not eligible (caller falls back)
+bool plane_gemm_mfma_eligible(const GemmDesc &g);
+hipError_t launch_plane_gemm_mfma(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s);
+
+}  // namespace stl

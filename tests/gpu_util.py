@@ -1,0 +1,68 @@
+"""Helpers for the GPU parity tests: upload seeded inputs, call the C ABI, download results."""
+import numpy as np
+import torch
+
+import paper_2503_12211_amd as stl
+
+TOL = {"f32": 1e-5, "bf16": 1e-2}          # relative Frobenius error bars (fp32 / bf16 with fp32 accumulation)
+TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
+STL_DT = {"f32": stl.STL_F32, "bf16": stl.STL_BF16}
+
+
+def rel(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def dev(a, dtype):
+    """float32 numpy values (already representable in dtype) -> device tensor of that dtype."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda").to(TORCH_DT[dtype]).contiguous()
+
+
+def host(t):
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def workspace(prob, op, flags=0):
+    nbytes = stl.stl_workspace_bytes(prob, op, flags)
+    return torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda"), nbytes
+
+
+def forward(p, dtype, flags=0, save_yhat=False):
+    """p: dict with X, What, E_X, D (numpy).  Returns C (and Yhat) as float64 numpy."""
+    m, k = p["X"].shape
+    r, K, N = p["What"].shape
+    n = 4 * N
+    prob = stl.Problem(m, k, n, r, STL_DT[dtype])
+    X, What, E_X, D = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D"))
+    C = torch.full((m, n), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
+    Y = torch.full((r, m // 4, N), float("nan"), dtype=TORCH_DT[dtype], device="cuda") if save_yhat else None
+    ws, nbytes = workspace(prob, stl.STL_OP_FORWARD, flags)
+    stl.stl_forward(prob, X, What, E_X, D, C, Y, ws, nbytes, flags)
+    torch.cuda.synchronize()
+    return (host(C), host(Y)) if save_yhat else host(C)
+
+
+def backward(p, dtype, yhat=None, accumulate=0, init=None, skip=()):
+    m, k = p["X"].shape
+    r, K, N = p["What"].shape
+    n = 4 * N
+    prob = stl.Problem(m, k, n, r, STL_DT[dtype])
+    X, What, E_X, D, dC = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D", "dC"))
+    Y = dev(yhat, dtype) if yhat is not None else None
+    dX = torch.full((m, k), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
+    f32 = dict(dtype=torch.float32, device="cuda")
+    if init is None:
+        dWhat = torch.full((r, K, N), float("nan"), **f32)
+        dE_X = torch.full((r, 16), float("nan"), **f32)
+        dD = torch.full((r, 16), float("nan"), **f32)
+    else:
+        dWhat, dE_X, dD = (torch.from_numpy(np.asarray(a, dtype=np.float32)).cuda() for a in init)
+    outs = {"dX": dX, "dWhat": dWhat, "dE_X": dE_X, "dD": dD}
+    args = {k_: (None if k_ in skip else v) for k_, v in outs.items()}
+    ws, nbytes = workspace(prob, stl.STL_OP_BACKWARD)
+    stl.stl_backward(prob, X, What, E_X, D, dC, Y, args["dX"], args["dWhat"], args["dE_X"], args["dD"],
+                     accumulate, ws, nbytes)
+    torch.cuda.synchronize()
+    return {k_: host(v) for k_, v in outs.items()}

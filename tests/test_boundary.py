@@ -1,0 +1,78 @@
+"""CPU-side checks of the C ABI: the library loads, exports what include/stl.h declares, and rejects
+bad arguments before any launch (no GPU needed: validation happens on the host)."""
+import re
+from pathlib import Path
+
+import pytest
+
+import paper_2503_12211_amd as stl
+
+ROOT = Path(__file__).resolve().parent.parent
+FAKE = 0x1000  # a non-null "device pointer"; never dereferenced because validation fails first
+
+
+def test_header_symbols_are_exported():
+    header = (ROOT / "include" / "stl.h").read_text()
+    declared = set(re.findall(r"\b(stl_[a-z_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    exported = set(stl.exported_symbols())
+    assert declared <= exported, declared - exported
+
+
+def test_version_and_status_strings():
+    assert "gfx950" in stl.stl_version()
+    assert stl.stl_status_string(0) == "ok"
+    assert stl.stl_status_string(3).startswith("workspace")
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(m=254), 1), (dict(k=0), 1), (dict(n=-4), 1), (dict(r=0), 1), (dict(r=65), 1),
+    (dict(t=8), 2), (dict(dtype=7), 2),
+])
+def test_invalid_problem_is_rejected(kw, status):
+    base = dict(m=256, k=256, n=256, r=32, dtype=stl.STL_BF16, t=4)
+    base.update(kw)
+    prob = stl.Problem(**base)
+    assert stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD) == 0
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, 1 << 40, 0, stream=0)
+    assert e.value.status == status
+    with pytest.raises(stl.StlError):
+        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, 0, FAKE, 1 << 40, stream=0)
+    with pytest.raises(stl.StlError):
+        stl.stl_encode_weight(prob, FAKE, FAKE, FAKE, stream=0)
+
+
+def test_null_pointers_and_workspace():
+    prob = stl.Problem(256, 256, 256, 32)
+    need = stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD, stl.STL_FLAG_UNFUSED)
+    assert need >= 2 * 32 * 64 * 64 * 2
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_forward(prob, None, FAKE, FAKE, FAKE, FAKE, None, FAKE, need, stl.STL_FLAG_UNFUSED, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, need - 1, stl.STL_FLAG_UNFUSED, stream=0)
+    assert e.value.status == 3 and "workspace" in str(e.value)
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, 0, stl.STL_FLAG_UNFUSED, stream=0)
+    assert e.value.status == 3
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, need, 0x4000, stream=0)
+    assert e.value.status == 2
+    bneed = stl.stl_workspace_bytes(prob, stl.STL_OP_BACKWARD)
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, FAKE, 0, FAKE, bneed, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, 2, FAKE, bneed, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, 0, FAKE, bneed - 1, stream=0)
+    assert e.value.status == 3
+
+
+def test_workspace_grows_with_problem():
+    a = stl.stl_workspace_bytes(stl.Problem(256, 256, 256, 32), stl.STL_OP_BACKWARD)
+    b = stl.stl_workspace_bytes(stl.Problem(512, 256, 256, 32), stl.STL_OP_BACKWARD)
+    assert 0 < a < b
+    assert stl.stl_workspace_bytes(stl.Problem(256, 256, 256, 32), stl.STL_OP_ENCODE_WEIGHT) == 0

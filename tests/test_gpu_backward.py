@@ -1,0 +1,116 @@
+"""GPU parity: stl_backward (dX, dWhat, dE_X, dD) against the fp64 oracle and finite differences."""
+import numpy as np
+import pytest
+
+import oracle
+import stl_synth
+from oracle import planes
+
+pytestmark = pytest.mark.gpu
+NAMES = ("dX", "dWhat", "dE_X", "dD")
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+    return gpu_util
+
+
+def oracle_grads(p, use_planes=False):
+    f = planes.backward if use_planes else oracle.backward
+    return dict(zip(NAMES, f(p["X"], p["What"], p["E_X"], p["D"], p["dC"])))
+
+
+SHAPES = [(4, 4, 4, 1), (20, 36, 28, 7), (68, 132, 76, 24), (160, 96, 224, 32), (32, 32, 32, 64)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_backward_small(gu, dtype, shape):
+    m, k, n, r = shape
+    p = stl_synth.stl_problem(m, k, n, r, seed=31 + m + r, dtype=dtype, with_dC=True)
+    got = gu.backward(p, dtype)
+    ref = oracle_grads(p)
+    for name in NAMES:
+        assert gu.rel(got[name], ref[name]) <= gu.TOL[dtype], name
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_finite_differences_32(gu, dtype):
+    """m=k=n=32: <grad, V> from the GPU equals the central difference of the fp64 forward along V
+    (the loss is linear in each argument, so the difference quotient has no truncation error)."""
+    p = stl_synth.stl_problem(32, 32, 32, 32, seed=41, dtype=dtype, with_dC=True)
+    got = gu.backward(p, dtype)
+    rng = np.random.default_rng(1)
+    keys = {"dX": "X", "dWhat": "What", "dE_X": "E_X", "dD": "D"}
+
+    def loss(q):
+        return float(np.sum(q["dC"].astype(np.float64) * oracle.forward(q["X"], q["What"], q["E_X"], q["D"])))
+
+    for g, a in keys.items():
+        V = rng.standard_normal(p[a].shape)
+        plus = {k_: v.astype(np.float64) for k_, v in p.items()}
+        minus = {k_: v.astype(np.float64) for k_, v in p.items()}
+        plus[a] = plus[a] + 1e-3 * V
+        minus[a] = minus[a] - 1e-3 * V
+        fd = (loss(plus) - loss(minus)) / 2e-3
+        an = float(np.sum(got[g] * V))
+        scale = np.linalg.norm(got[g]) * np.linalg.norm(V)
+        assert abs(fd - an) <= gu.TOL[dtype] * scale, (g, fd, an)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_256_slice(gu, dtype):
+    """The 256 x 256 x 256 sub-problem with the workload's distributions, r=32."""
+    p = stl_synth.stl_problem(256, 256, 256, 32, seed=51, dtype=dtype, with_dC=True)
+    got = gu.backward(p, dtype)
+    ref = oracle_grads(p)
+    for name in NAMES:
+        assert gu.rel(got[name], ref[name]) <= gu.TOL[dtype], name
+    # Euler identities: the loss is homogeneous of degree one in every argument
+    lhs = [np.sum(got["dX"] * p["X"]), np.sum(got["dWhat"] * p["What"]), np.sum(got["dE_X"] * p["E_X"]),
+           np.sum(got["dD"] * p["D"])]
+    val = np.sum(p["dC"].astype(np.float64) * oracle.forward(p["X"], p["What"], p["E_X"], p["D"]))
+    scale = np.linalg.norm(p["dC"]) * np.linalg.norm(oracle.forward(p["X"], p["What"], p["E_X"], p["D"]))
+    for v in lhs:
+        assert abs(v - val) <= gu.TOL[dtype] * scale
+
+
+def test_backward_saved_yhat_accumulate_and_skips(gu):
+    dtype = "bf16"
+    p = stl_synth.stl_problem(96, 160, 128, 16, seed=61, dtype=dtype, with_dC=True)
+    ref = oracle_grads(p)
+    C, Y = gu.forward(p, dtype, save_yhat=True)
+    with_saved = gu.backward(p, dtype, yhat=Y)
+    for name in NAMES:
+        assert gu.rel(with_saved[name], ref[name]) <= gu.TOL[dtype], name
+    rng = np.random.default_rng(2)
+    init = [rng.standard_normal(ref[nm].shape).astype(np.float32) for nm in ("dWhat", "dE_X", "dD")]
+    acc = gu.backward(p, dtype, accumulate=1, init=init)
+    for nm, i0 in zip(("dWhat", "dE_X", "dD"), init):
+        assert gu.rel(acc[nm] - i0, ref[nm]) <= gu.TOL[dtype], nm
+    part = gu.backward(p, dtype, skip=("dX", "dD"))
+    assert np.isnan(part["dX"]).all() and np.isnan(part["dD"]).all()       # untouched
+    assert gu.rel(part["dWhat"], ref["dWhat"]) <= gu.TOL[dtype]
+    assert gu.rel(part["dE_X"], ref["dE_X"]) <= gu.TOL[dtype]
+
+
+def test_backward_matrix_core_shapes_bf16(gu):
+    """Plane sizes that take the MFMA kernels in all three products, with ragged blocks."""
+    p = stl_synth.stl_problem(1056, 544, 800, 8, seed=71, dtype="bf16", with_dC=True)
+    got = gu.backward(p, "bf16")
+    ref = oracle_grads(p, use_planes=True)
+    for name in NAMES:
+        assert gu.rel(got[name], ref[name]) <= gu.TOL["bf16"], name
+    again = gu.backward(p, "bf16")
+    for name in NAMES:
+        assert np.array_equal(got[name], again[name]), name        # bitwise reproducible
+
+
+def test_config5_full_size(gu):
+    """bf16, m=8192, k=n=4096, r=32, forward + backward at full size against the plane oracle."""
+    cfg, p = stl_synth.config_problem("C5", with_dC=True)
+    got = gu.backward(p, "bf16")
+    ref = oracle_grads(p, use_planes=True)
+    for name in NAMES:
+        assert gu.rel(got[name], ref[name]) <= gu.TOL["bf16"], name

@@ -1,0 +1,143 @@
+"""GPU parity: stl_forward / stl_encode_weight / the three stage entry points against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import stl_synth
+from oracle import bases, planes
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+    return gpu_util
+
+
+def test_config1_fp32_strassen_exact(gu):
+    """fp32, m=k=n=256, r=49 two-level Strassen basis: output equals X.W to fp32 rounding."""
+    import paper_2503_12211_amd as stl
+    cfg, p = stl_synth.config_problem("C1")
+    E_X, E_W, D = bases.strassen_4x4()
+    prob = stl.Problem(256, 256, 256, 49, stl.STL_F32)
+    W = gu.dev(p["W"], "f32")
+    What = torch.empty((49, 64, 64), dtype=torch.float32, device="cuda")
+    stl.stl_encode_weight(prob, W, gu.dev(E_W, "f32"), What)
+    torch.cuda.synchronize()
+    What_ref = oracle.encode_weight(p["W"], E_W)
+    assert gu.rel(gu.host(What), What_ref) <= 1e-6
+    q = {"X": p["X"], "What": gu.host(What), "E_X": E_X, "D": D}
+    C = gu.forward(q, "f32")
+    ref = oracle.forward(p["X"], What_ref, E_X, D)
+    exact = p["X"].astype(np.float64) @ p["W"].astype(np.float64)
+    assert gu.rel(ref, exact) < 1e-13
+    assert gu.rel(C, ref) <= gu.TOL["f32"]
+    assert gu.rel(C, exact) <= gu.TOL["f32"]
+
+
+SMALL = [  # (m, k, n, r): single tile, ragged everything, several blocks + ragged tail
+    (4, 4, 4, 1), (4, 8, 4, 64), (20, 36, 28, 7), (68, 132, 76, 24), (260, 132, 520, 32), (132, 260, 68, 49),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", SMALL)
+def test_forward_small_and_ragged(gu, dtype, shape):
+    m, k, n, r = shape
+    p = stl_synth.stl_problem(m, k, n, r, seed=11 + m + r, dtype=dtype)
+    C = gu.forward(p, dtype)
+    ref = oracle.forward(p["X"], p["What"], p["E_X"], p["D"])
+    assert gu.rel(C, ref) <= gu.TOL[dtype]
+
+
+MFMA_SHAPES = [  # tile counts are multiples of 8 (matrix-core path), not multiples of the block sizes
+    (1056, 544, 800, 5), (512, 1024, 512, 32), (288, 2080, 1312, 16), (2048, 256, 96, 64), (32, 32, 32, 3),
+    (1024, 512, 1056, 49),
+]
+
+
+@pytest.mark.parametrize("shape", MFMA_SHAPES)
+def test_forward_bf16_matrix_core_shapes(gu, shape):
+    m, k, n, r = shape
+    p = stl_synth.stl_problem(m, k, n, r, seed=23 + n + r, dtype="bf16")
+    C, Y = gu.forward(p, "bf16", save_yhat=True)
+    Cref, Yref = planes.forward(p["X"], p["What"], p["E_X"], p["D"], return_yhat=True)
+    assert gu.rel(Y, Yref) <= gu.TOL["bf16"]
+    assert gu.rel(C, Cref) <= gu.TOL["bf16"]
+    # literal Eq. (2) on a ragged corner block
+    M, N = m // 4, n // 4
+    blk = oracle.forward_block(p["X"], p["What"], p["E_X"], p["D"], max(M - 5, 0), M, max(N - 3, 0), N)
+    assert gu.rel(C[4 * max(M - 5, 0):, 4 * max(N - 3, 0):], blk) <= 2 * gu.TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stage_entry_points(gu, dtype):
+    """Each of Algorithm 1's three steps against the oracle's step, fed the same (rounded) operands."""
+    import paper_2503_12211_amd as stl
+    m, k, n, r = 136, 264, 72, 24
+    p = stl_synth.stl_problem(m, k, n, r, seed=5, dtype=dtype)
+    prob = stl.Problem(m, k, n, r, gu.STL_DT[dtype])
+    tdt = gu.TORCH_DT[dtype]
+    X, What, E_X, D = (gu.dev(p[s], dtype) for s in ("X", "What", "E_X", "D"))
+    Xhat = torch.empty((r, m // 4, k // 4), dtype=tdt, device="cuda")
+    stl.stl_encode_activation(prob, X, E_X, Xhat)
+    torch.cuda.synchronize()
+    assert gu.rel(gu.host(Xhat), oracle.encode_x(p["X"], p["E_X"])) <= gu.TOL[dtype]
+    Yhat = torch.empty((r, m // 4, n // 4), dtype=tdt, device="cuda")
+    stl.stl_plane_matmul(prob, Xhat, What, Yhat)
+    torch.cuda.synchronize()
+    assert gu.rel(gu.host(Yhat), planes.plane_products(gu.host(Xhat), p["What"])) <= gu.TOL[dtype]
+    C = torch.empty((m, n), dtype=tdt, device="cuda")
+    stl.stl_decode(prob, Yhat, D, C)
+    torch.cuda.synchronize()
+    assert gu.rel(gu.host(C), planes.decode(gu.host(Yhat), p["D"])) <= gu.TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_gelu_epilogue(gu, dtype):
+    import paper_2503_12211_amd as stl
+    p = stl_synth.stl_problem(64, 96, 160, 24, seed=9, dtype=dtype)
+    C = gu.forward(p, dtype, flags=stl.STL_FLAG_GELU)
+    ref = planes.gelu(oracle.forward(p["X"], p["What"], p["E_X"], p["D"]))
+    assert gu.rel(C, ref) <= gu.TOL[dtype]
+
+
+def test_exact_bases_bf16_inputs(gu):
+    """bf16 storage, trivial r=64 basis, small-integer inputs: every intermediate is exactly
+    representable, so the result must equal X.W exactly."""
+    import paper_2503_12211_amd as stl
+    rng = np.random.default_rng(3)
+    m, k, n = 64, 32, 96
+    X = rng.integers(-3, 4, size=(m, k)).astype(np.float32)
+    W = rng.integers(-2, 3, size=(k, n)).astype(np.float32)
+    E_X, E_W, D = bases.trivial(4)
+    prob = stl.Problem(m, k, n, 64, stl.STL_BF16)
+    What = torch.empty((64, k // 4, n // 4), dtype=torch.bfloat16, device="cuda")
+    stl.stl_encode_weight(prob, gu.dev(W, "bf16"), gu.dev(E_W, "bf16"), What)
+    C = gu.forward({"X": X, "What": gu.host(What), "E_X": E_X, "D": D}, "bf16")
+    assert np.array_equal(C, (X @ W).astype(np.float64))
+
+
+def test_config2_full_size(gu):
+    """bf16, m=k=n=4096, r=32 at full size: whole output against the plane oracle, and sampled
+    8x8-tile blocks against literal Eq. (2)."""
+    cfg, p = stl_synth.config_problem("C2")
+    C = gu.forward(p, "bf16")
+    Cref = planes.forward(p["X"], p["What"], p["E_X"], p["D"])
+    assert gu.rel(C, Cref) <= gu.TOL["bf16"]
+    rng = np.random.default_rng(0)
+    for _ in range(3):
+        I0, J0 = (int(v) for v in rng.integers(0, 1024 - 8, size=2))
+        blk = oracle.forward_block(p["X"], p["What"], p["E_X"], p["D"], I0, I0 + 8, J0, J0 + 8)
+        assert gu.rel(C[4 * I0:4 * I0 + 32, 4 * J0:4 * J0 + 32], blk) <= 2 * gu.TOL["bf16"]
+    # statistical property of the workload: Var C = sum_p |D_p|^2 |E_p|^2-weighted, order r/64
+    assert 0.2 < C.var() / (32 / 64) < 5.0
+
+
+def test_forward_is_deterministic(gu):
+    p = stl_synth.stl_problem(512, 512, 512, 32, seed=77, dtype="bf16")
+    a = gu.forward(p, "bf16")
+    b = gu.forward(p, "bf16")
+    assert np.array_equal(a, b)

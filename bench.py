@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the STL hot path on one MI355X.
+
+A step is one pass of the whole hot path -- stl_forward (encode -> plane products -> decode, saving
+Yhat) followed by stl_backward (dX, dWhat, dE_X, dD) -- on the forward+backward workload of the
+workload list: bf16, m=8192, k=n=4096, t=4, r=32, inputs resident in HBM.  The same step is timed
+for a dense bf16 GEMM of the same m, k, n (torch.matmul: X.W, dC.W^T, X^T.dC) on the same GPU.
+
+Prints ONE JSON line on stdout (details go to stderr).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C5", help="C5 (default), C2, or m,k,n,r")
+    ap.add_argument("--sweep", action="store_true", help="also time the forward r sweep (m=8192,k=n=4096)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-only", default="", help="run only this leg (forward|backward|stages) a few times")
+    return ap.parse_args()
+
+
+def flops_model(m, k, n, r):
+    """FLOPs actually executed by this implementation per forward / backward."""
+    M, K, N = m // 4, k // 4, n // 4
+    gemm = 2.0 * r * M * K * N
+    fwd = gemm + 2.0 * m * k * r + 2.0 * m * n * r
+    # backward: encode X, encode dC, two plane products, decode dX, two basis-gradient reductions
+    bwd = 2 * gemm + 2.0 * m * k * r + 2.0 * m * n * r + 2.0 * m * k * r + 2.0 * 16 * r * (M * N + M * K)
+    return gemm, fwd, bwd
+
+
+class Timer:
+    def __init__(self, torch):
+        self.torch = torch
+
+    def wall(self, fn, steps, warmup):
+        t = self.torch
+        for _ in range(warmup):
+            fn()
+        t.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        t.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def events(self, fn, steps, warmup):
+        """Average per-launch duration between two events on the current stream (the stream the
+        library launches on)."""
+        t = self.torch
+        for _ in range(warmup):
+            fn()
+        t.cuda.synchronize()
+        e0, e1 = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        t.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; rerun with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2503_12211_amd as stl
+    import stl_synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    T = Timer(torch)
+
+    if args.workload in stl_synth.CONFIGS:
+        cfg = stl_synth.CONFIGS[args.workload]
+        m, k, n, r = cfg["m"], cfg["k"], cfg["n"], cfg["r"]
+        seed = stl_synth.SEEDS[args.workload]
+        wname = args.workload
+    else:
+        m, k, n, r = (int(v) for v in args.workload.split(","))
+        seed, wname = 4242, f"custom_{m}x{k}x{n}_r{r}"
+    M, K, N = m // 4, k // 4, n // 4
+    p = stl_synth.stl_problem(m, k, n, r, seed, "bf16", with_dC=True)
+    bf = torch.bfloat16
+
+    def dev(a):
+        return torch.from_numpy(a).cuda().to(bf).contiguous()
+
+    X, What, E_X, D, dC = (dev(p[s]) for s in ("X", "What", "E_X", "D", "dC"))
+    prob = stl.Problem(m, k, n, r, stl.STL_BF16)
+    C = torch.empty((m, n), dtype=bf, device="cuda")
+    Yhat = torch.empty((r, M, N), dtype=bf, device="cuda")
+    Xhat = torch.empty((r, M, K), dtype=bf, device="cuda")
+    dX = torch.empty((m, k), dtype=bf, device="cuda")
+    dWhat = torch.empty((r, K, N), dtype=torch.float32, device="cuda")
+    dE_X = torch.empty((r, 16), dtype=torch.float32, device="cuda")
+    dD = torch.empty((r, 16), dtype=torch.float32, device="cuda")
+    nf = stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD, stl.STL_FLAG_AUTO)
+    nb = stl.stl_workspace_bytes(prob, stl.STL_OP_BACKWARD)
+    ws_f = torch.empty(max(nf, 16), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(max(nb, 16), dtype=torch.uint8, device="cuda")
+
+    def fwd():
+        stl.stl_forward(prob, X, What, E_X, D, C, Yhat, ws_f, nf, stl.STL_FLAG_AUTO)
+
+    def fwd_nosave():
+        stl.stl_forward(prob, X, What, E_X, D, C, None, ws_f, nf, stl.STL_FLAG_AUTO)
+
+    def bwd():
+        stl.stl_backward(prob, X, What, E_X, D, dC, Yhat, dX, dWhat, dE_X, dD, 0, ws_b, nb)
+
+    def step():
+        fwd()
+        bwd()
+
+    if args.profile_only:
+        legs = {"forward": fwd_nosave, "backward": bwd, "step": step,
+                "stages": lambda: (stl.stl_encode_activation(prob, X, E_X, Xhat),
+                                   stl.stl_plane_matmul(prob, Xhat, What, Yhat),
+                                   stl.stl_decode(prob, Yhat, D, C))}
+        fwd()
+        for _ in range(max(args.steps, 1)):
+            legs[args.profile_only]()
+        torch.cuda.synchronize()
+        return
+
+    # dense comparison: same m, k, n, bf16, same GPU, same protocol
+    Wd = (torch.randn((k, n), device="cuda") * k ** -0.5).to(bf)
+
+    def dense_fwd():
+        torch.matmul(X, Wd, out=C)
+
+    dXd = torch.empty((m, k), dtype=bf, device="cuda")
+    dWd = torch.empty((k, n), dtype=bf, device="cuda")
+
+    def dense_step():
+        torch.matmul(X, Wd, out=C)
+        torch.matmul(dC, Wd.t(), out=dXd)
+        torch.matmul(X.t(), dC, out=dWd)
+
+    W, S = args.warmup, args.steps
+    ms_step = T.wall(step, S, W)
+    ms_dense_step = T.wall(dense_step, S, W)
+    ms_fwd = T.wall(fwd_nosave, S, W)
+    ms_bwd = T.wall(bwd, S, W)
+    ms_dense_fwd = T.wall(dense_fwd, S, W)
+
+    # stage timings with events on the launch stream
+    ms_enc = T.events(lambda: stl.stl_encode_activation(prob, X, E_X, Xhat), S, W)
+    ms_gemm = T.events(lambda: stl.stl_plane_matmul(prob, Xhat, What, Yhat), S, W)
+    ms_dec = T.events(lambda: stl.stl_decode(prob, Yhat, D, C), S, W)
+
+    gemm_flop, fwd_flop, bwd_flop = flops_model(m, k, n, r)
+    dense_flop = 2.0 * m * k * n
+    tf = lambda fl, ms: fl / (ms * 1e-3) / 1e12
+    enc_bytes = 2.0 * (m * k + r * M * K)
+    dec_bytes = 2.0 * (r * M * N + m * n)
+
+    log(f"workload {wname}: m={m} k={k} n={n} r={r} bf16")
+    log(f"  STL  fwd {ms_fwd:.4f} ms  bwd {ms_bwd:.4f} ms  step {ms_step:.4f} ms  "
+        f"({tf(fwd_flop + bwd_flop, ms_step):.1f} TFLOP/s executed)")
+    log(f"  dense fwd {ms_dense_fwd:.4f} ms ({tf(dense_flop, ms_dense_fwd):.1f} TFLOP/s)  step {ms_dense_step:.4f} ms")
+    log(f"  stages: encode {ms_enc:.4f} ms ({enc_bytes / ms_enc / 1e6:.0f} GB/s)  plane products {ms_gemm:.4f} ms "
+        f"({tf(gemm_flop, ms_gemm):.1f} TFLOP/s, {100 * tf(gemm_flop, ms_gemm) / PEAK_BF16_TFLOPS:.1f}% of bf16 peak)  "
+        f"decode {ms_dec:.4f} ms ({dec_bytes / ms_dec / 1e6:.0f} GB/s)")
+
+    out = {
+        "metric": "STL fwd+bwd wall time vs dense bf16 GEMM same shape; MFMA util %",
+        "value": round(ms_dense_step / ms_step, 4),
+        "unit": "x (dense bf16 GEMM fwd+bwd wall time / STL fwd+bwd wall time, same m,k,n, same GPU)",
+        "n_gpus": 1, "steps": S, "warmup": W, "ms_per_step": round(ms_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wname}: STL forward+backward, m={m}, k={k}, n={n}, t=4, r={r}, bf16 in / fp32 accumulate",
+                   "m": m, "k": k, "n": n, "t": 4, "r": r},
+        "stl_ms": {"forward": round(ms_fwd, 5), "backward": round(ms_bwd, 5), "step": round(ms_step, 5)},
+        "dense_ms": {"forward": round(ms_dense_fwd, 5), "step": round(ms_dense_step, 5)},
+        "forward_speedup_vs_dense": round(ms_dense_fwd / ms_fwd, 4),
+        "stl_tflops_executed": round(tf(fwd_flop + bwd_flop, ms_step), 2),
+        "dense_tflops": round(tf(3 * dense_flop, ms_dense_step), 2),
+        "mfma_util_pct": round(100 * tf(gemm_flop, ms_gemm) / PEAK_BF16_TFLOPS, 2),
+        "stages": {
+            "encode": {"ms": round(ms_enc, 5), "GBps": round(enc_bytes / ms_enc / 1e6, 1),
+                       "frac_hbm_peak": round(enc_bytes / ms_enc / 1e6 / PEAK_HBM_GBS, 4)},
+            "plane_products": {"ms": round(ms_gemm, 5), "TFLOPs": round(tf(gemm_flop, ms_gemm), 2)},
+            "decode": {"ms": round(ms_dec, 5), "GBps": round(dec_bytes / ms_dec / 1e6, 1),
+                       "frac_hbm_peak": round(dec_bytes / ms_dec / 1e6 / PEAK_HBM_GBS, 4)},
+        },
+        "roofline": {"kernel": "gemm_mfma_kernel (forward plane products, one launch)", "bound": "mfma",
+                     "achieved": round(tf(gemm_flop, ms_gemm), 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tf(gemm_flop, ms_gemm) / PEAK_BF16_TFLOPS, 4), "traffic": None},
+    }
+
+    if args.sweep:
+        sweep = {}
+        for rr in (8, 16, 24, 32, 49, 64):
+            q = stl_synth.stl_problem(8192, 4096, 4096, rr, 1003 + 100 * rr, "bf16")
+            Xs, Ws, Es, Ds = (dev(q[s]) for s in ("X", "What", "E_X", "D"))
+            pr = stl.Problem(8192, 4096, 4096, rr, stl.STL_BF16)
+            Cs = torch.empty((8192, 4096), dtype=bf, device="cuda")
+            nbs = stl.stl_workspace_bytes(pr, stl.STL_OP_FORWARD, 0)
+            wss = torch.empty(nbs, dtype=torch.uint8, device="cuda")
+            ms = T.wall(lambda: stl.stl_forward(pr, Xs, Ws, Es, Ds, Cs, None, wss, nbs, 0), S, W)
+            sweep[str(rr)] = round(ms, 5)
+            log(f"  sweep r={rr}: forward {ms:.4f} ms")
+            del Xs, Ws, Es, Ds, Cs, wss
+        Wd2 = torch.randn((4096, 4096), device="cuda").to(bf)
+        X2 = torch.randn((8192, 4096), device="cuda").to(bf)
+        C2 = torch.empty((8192, 4096), dtype=bf, device="cuda")
+        sweep["dense"] = round(T.wall(lambda: torch.matmul(X2, Wd2, out=C2), S, W), 5)
+        out["forward_r_sweep_ms_m8192_k4096_n4096"] = sweep
+
+    if not args.no_cpu_baseline:
+        import oracle
+        sm = 2048                                  # bounded sample: the m=k=n=2048 sub-problem, same r and distributions
+        q = stl_synth.stl_problem(sm, sm, sm, r, seed + 1, "bf16", with_dC=True)
+        t0 = time.perf_counter()
+        oracle.forward(q["X"], q["What"], q["E_X"], q["D"])
+        oracle.backward(q["X"], q["What"], q["E_X"], q["D"], q["dC"])
+        dt = time.perf_counter() - t0
+        scale = (m / sm) * (k / sm) * (n / sm)
+        full_ms = dt * scale * 1e3
+        out["cpu_baseline"] = {
+            "value": round(ms_dense_step / full_ms, 8), "unit": out["unit"], "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"fp64 oracle (literal Eq. 2 forward + chain-rule backward, gcc -O2 OpenMP) on the "
+                      f"m=k=n={sm}, r={r} sub-problem: {dt:.2f} s; scaled by m*k*n ratio {scale:.0f} to the full "
+                      f"workload = {full_ms / 1e3:.0f} s per step (extrapolated)",
+            "oracle_seconds_sample": round(dt, 3),
+        }
+        log(f"  cpu oracle: {dt:.2f} s on {sm}^3 sample with {oracle.num_threads()} threads")
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -13,6 +13,8 @@
 #include "stl_kernels.h"
 #include "stl_device.h"
 
+#include <cstdlib>
+
 namespace stl {
 
 constexpr int BK = 64;  // contraction elements per LDS stage (one 128-byte LDS row)
@@ -178,22 +180,46 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(const 
         __syncthreads();
     }
 
-    // accumulator layout of the 32x32 fragment: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4
+    // Epilogue.  Accumulator layout of a 32x32 fragment: column = lane % 32,
+    // row = 8*(v/4) + 4*(lane/32) + v%4.  Each wavefront passes 32 rows x WN columns at a time
+    // through its own LDS slab so that HBM sees whole 16-byte, row-contiguous stores.
+    constexpr int ES = sizeof(TO);
+    constexpr int PITCH = WN * ES + 16;                 // bytes per staged row (+16: spreads rows over banks)
+    constexpr int LPR = WN * ES / 16;                   // lanes per row in the store phase
+    constexpr int RPI = 64 / LPR;                       // rows per store instruction
+    char *slab = smem + wave * (32 * PITCH);
+    static_assert(32 * PITCH * WAVES_M * WAVES_N <= 2 * STAGE, "epilogue slab does not fit");
 #pragma unroll
-    for (int a = 0; a < FM; ++a)
+    for (int a = 0; a < FM; ++a) {
+        __syncthreads();
 #pragma unroll
-        for (int b = 0; b < FN; ++b) {
-            const int gj = j0 + wn * WN + b * 32 + frow;
+        for (int b = 0; b < FN; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int gi = i0 + wm * WM + a * 32 + 8 * (v >> 2) + 4 * fhalf + (v & 3);
-                if (gi < Mi && gj < Nj) {
-                    TO *o = Out + (size_t)gi * Nj + gj;
-                    if (ACC) Elem<TO>::st(o, Elem<TO>::ld(o) + acc[a][b][v]);
-                    else Elem<TO>::st(o, acc[a][b][v]);
+                const int rr = 8 * (v >> 2) + 4 * fhalf + (v & 3), cc = b * 32 + frow;
+                Elem<TO>::st(reinterpret_cast<TO *>(slab + rr * PITCH) + cc, acc[a][b][v]);
+            }
+        __syncthreads();
+        const int gi_base = i0 + wm * WM + a * 32;
+        const int gj = j0 + wn * WN + (lane % LPR) * (16 / ES);
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int rr = it * RPI + lane / LPR;
+            const int gi = gi_base + rr;
+            if (gi < Mi && gj < Nj) {
+                u32x4_t w = *reinterpret_cast<const u32x4_t *>(slab + rr * PITCH + (lane % LPR) * 16);
+                TO *o = Out + (size_t)gi * Nj + gj;
+                if (ACC) {
+                    const f32x4_t old = *reinterpret_cast<const f32x4_t *>(o);
+                    f32x4_t nw = __builtin_bit_cast(f32x4_t, w);
+                    nw += old;
+                    *reinterpret_cast<f32x4_t *>(o) = nw;
+                } else {
+                    *reinterpret_cast<u32x4_t *>(o) = w;
                 }
             }
         }
+    }
 }
 
 // ---- host side ---------------------------------------------------------------------------
@@ -205,8 +231,7 @@ bool plane_gemm_mfma_eligible(const GemmDesc &g)
     // weight gradient [l][i]x[l][j] (fp32 out)
     if (g.out_f32 ? !(g.a_kmajor && g.b_kmajor) : g.a_kmajor) return false;
     // 16-byte global loads along each operand's contiguous dimension
-    if ((g.a_kmajor ? g.Mi : g.Kl) % 8) return false;
-    if ((g.b_kmajor ? g.Nj : g.Kl) % 8) return false;
+    if (g.Mi % 8 || g.Nj % 8 || g.Kl % 8) return false;
     return true;
 }
 
@@ -233,9 +258,16 @@ static hipError_t launch_cfg(const GemmDesc &g, const void *A, const void *B, vo
 template <bool A_T, bool B_T, typename TO, bool ACC>
 static hipError_t launch_shape(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
-    // large planes: 256x256 blocks, 8 wavefronts (2 x 4), 128x64 per wavefront
-    if (g.Mi > 128 && g.Nj > 128) return launch_cfg<256, 256, 2, 4, A_T, B_T, TO, ACC>(g, A, B, Out, s);
-    return launch_cfg<128, 128, 2, 2, A_T, B_T, TO, ACC>(g, A, B, Out, s);
+    static const int forced = []() { const char *e = getenv("STL_GEMM_CFG"); return e ? atoi(e) : -1; }();
+    int cfg = forced;
+    if (cfg < 0) cfg = (g.Mi > 128 && g.Nj > 128) ? 0 : 2;
+    switch (cfg) {
+        case 0: return launch_cfg<256, 256, 2, 4, A_T, B_T, TO, ACC>(g, A, B, Out, s);   // 8 wavefronts, 128x64 each
+        case 1: return launch_cfg<256, 256, 2, 2, A_T, B_T, TO, ACC>(g, A, B, Out, s);   // 4 wavefronts, 128x128 each
+        case 3: return launch_cfg<256, 128, 2, 2, A_T, B_T, TO, ACC>(g, A, B, Out, s);   // 4 wavefronts, 128x64 each
+        case 4: return launch_cfg<128, 256, 2, 2, A_T, B_T, TO, ACC>(g, A, B, Out, s);   // 4 wavefronts, 64x128 each
+        default: return launch_cfg<128, 128, 2, 2, A_T, B_T, TO, ACC>(g, A, B, Out, s);  // 4 wavefronts, 64x64 each
+    }
 }
 
 hipError_t launch_plane_gemm_mfma(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)

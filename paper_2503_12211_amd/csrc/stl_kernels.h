@@ -14,7 +14,6 @@ hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, i
                          hipStream_t s);
 
 // G[p][q] (+)= sum_tiles P[p][tile] * tileview(V)[tile][q]; `part` holds outer_reduce_blocks(R*Cc) * r * 16 floats
-enum { OUTER_TILES_PER_BLOCK = 8192 };
 int outer_reduce_blocks(int64_t tiles);
 hipError_t launch_outer_reduce(int dtype, const void *P, const void *V, float *G, float *part, int R, int Cc, int r,
                                int accumulate, hipStream_t s);

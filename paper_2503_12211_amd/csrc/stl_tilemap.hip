@@ -120,11 +120,154 @@ __global__ __launch_bounds__(256) void outer_partial_kernel(const T *__restrict_
 __global__ __launch_bounds__(256) void outer_final_kernel(const float *__restrict__ part, float *__restrict__ G,
                                                           int nblocks, int n_out, int accumulate)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_out) return;
+    // 16 outputs per block; 16 slices of the block range per output, then a fixed-order sum.
+    __shared__ float red[16][17];
+    const int o = threadIdx.x & 15, sl = threadIdx.x >> 4;
+    const int i = blockIdx.x * 16 + o;
     float s = 0.f;
-    for (int b = 0; b < nblocks; ++b) s += part[(size_t)b * n_out + i];
-    G[i] = accumulate ? G[i] + s : s;
+    if (i < n_out)
+        for (int b = sl; b < nblocks; b += 16) s += part[(size_t)b * n_out + i];
+    red[sl][o] = s;
+    __syncthreads();
+    if (sl == 0 && i < n_out) {
+        float tot = 0.f;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) tot += red[u][o];
+        G[i] = accumulate ? G[i] + tot : tot;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// bf16 encode on the matrix cores.  The map "16 tile entries -> r planes" is a small dense
+// contraction (K = 16); on the vector ALUs it costs as many cycles as the HBM transfer, on
+// MFMA it is free and the kernel is bound by the stream through HBM alone.
+//   v_mfma_f32_32x32x16_bf16:  rows = planes (E, 32 x 16), columns = tiles (tile entries, 16 x 32).
+// A wavefront takes 128 consecutive tiles of one tile row: lane (j, h) loads rows 2h and 2h+1 of
+// tiles 4j..4j+3 (32 contiguous bytes each); MFMA u works on tiles 4j+u, so that afterwards a lane
+// holds 4 consecutive tiles of a plane and writes them with one 8-byte store.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void encode_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ E,
+                                                          bf16_t *__restrict__ P, int R, int Cc, int r, int chunks)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long item = (long)blockIdx.x * 4 + wave;          // (tile row, chunk of 128 tile columns)
+    if (item >= (long)R * chunks) return;
+    const int I = (int)(item / chunks), J0 = (int)(item % chunks) * 128;
+    const int j = lane & 31, h = lane >> 5;
+    const size_t ld = (size_t)Cc * 4;
+    const int Jl = J0 + 4 * j;                               // first of this lane's 4 tiles
+
+    u32x4_t row[2][2];                                       // [row 2h / 2h+1][tiles (0,1) / (2,3)]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            u32x4_t z = {0u, 0u, 0u, 0u};
+            if (Jl + 2 * c < Cc)
+                z = *reinterpret_cast<const u32x4_t *>(A + ((size_t)I * 4 + 2 * h + a) * ld + (size_t)(Jl + 2 * c) * 4);
+            row[a][c] = z;
+        }
+
+    const size_t plane = (size_t)R * Cc;
+    for (int g = 0; g < r; g += 32) {
+        const int pl = g + j;
+        u32x4_t ev = {0u, 0u, 0u, 0u};
+        if (pl < r) ev = *reinterpret_cast<const u32x4_t *>(E + pl * 16 + 8 * h);
+        const bf16x8_t ea = __builtin_bit_cast(bf16x8_t, ev);
+        f32x16_t acc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const u32x4_t bv = {row[0][u >> 1][2 * (u & 1)], row[0][u >> 1][2 * (u & 1) + 1],
+                                row[1][u >> 1][2 * (u & 1)], row[1][u >> 1][2 * (u & 1) + 1]};
+            f32x16_t zero;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+            acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ea, __builtin_bit_cast(bf16x8_t, bv), zero, 0, 0, 0);
+        }
+        if (Jl < Cc) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int po = g + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (po < r) {
+                    u32x2_t w = {pack_bf16x2(acc[0][v], acc[1][v]), pack_bf16x2(acc[2][v], acc[3][v])};
+                    *reinterpret_cast<u32x2_t *>(P + (size_t)po * plane + (size_t)I * Cc + Jl) = w;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// bf16 basis gradients on the matrix cores:  G (r x 16) = P (r x T) . tileview(V) (T x 16),
+// contraction over all T = R*Cc tiles, v_mfma_f32_16x16x32_bf16 (rows = planes, columns = the 16
+// tile entries, K = 32 tiles).  P fragments come straight from HBM (8 consecutive tiles of a plane
+// = 16 bytes); V is read coalesced and turned into "entry x tile" form through LDS.
+// Stage 1 writes one partial per block in a fixed order; stage 2 adds them in block order.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restrict__ P, const bf16_t *__restrict__ V,
+                                                         float *__restrict__ part, int R, int Cc, int r,
+                                                         int tiles_per_block)
+{
+    constexpr int PITCH = 64 + 8;                       // bf16 elements per LDS row (16-byte aligned rows)
+    __shared__ __align__(16) bf16_t sV[4][16][PITCH];
+    __shared__ float red[4][64 * 16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long T = (long)R * Cc;
+    const long t0 = (long)blockIdx.x * tiles_per_block;
+    long t1 = t0 + tiles_per_block;
+    if (t1 > T) t1 = T;
+    const size_t ld = (size_t)Cc * 4;
+    const int q = lane & 15, kq = lane >> 4;
+    const int ngroups = (r + 15) >> 4;
+
+    f32x4_t acc[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) acc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (long base = t0; base < t1; base += 256) {       // uniform trip count over the block
+        const long tb = base + wave * 64;
+        const long tile = tb + lane;
+        u32x2_t v[4];
+        if (tile < t1) {
+            const long I = tile / Cc, J = tile - I * Cc;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) v[a] = *reinterpret_cast<const u32x2_t *>(V + ((size_t)I * 4 + a) * ld + (size_t)J * 4);
+        } else {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) v[a] = u32x2_t{0u, 0u};
+        }
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            sV[wave][4 * a + 0][lane] = (bf16_t)(v[a][0] & 0xffffu);
+            sV[wave][4 * a + 1][lane] = (bf16_t)(v[a][0] >> 16);
+            sV[wave][4 * a + 2][lane] = (bf16_t)(v[a][1] & 0xffffu);
+            sV[wave][4 * a + 3][lane] = (bf16_t)(v[a][1] >> 16);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const bf16x8_t fb = *reinterpret_cast<const bf16x8_t *>(&sV[wave][q][32 * s + 8 * kq]);
+            const long tk = tb + 32 * s + 8 * kq;        // 8 consecutive tiles; all inside or all outside (T % 8 == 0)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                if (g < ngroups) {
+                    const int pl = 16 * g + q;
+                    u32x4_t av = {0u, 0u, 0u, 0u};
+                    if (pl < r && tk < t1) av = *reinterpret_cast<const u32x4_t *>(P + (size_t)pl * T + tk);
+                    acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av), fb, acc[g], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    // accumulator element e of group g: plane 16g + 4*(lane/16) + e, tile entry lane%16
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) red[wave][(16 * g + 4 * kq + e) * 16 + q] = acc[g][e];
+    __syncthreads();
+    for (int i = threadIdx.x; i < r * 16; i += 256)
+        part[(size_t)blockIdx.x * r * 16 + i] = ((red[0][i] + red[1][i]) + red[2][i]) + red[3][i];
 }
 
 // ---------------------------------------------------------------------------------------
@@ -140,6 +283,13 @@ static hipError_t launch_encode_t(const void *A, const void *E, void *P, int R, 
 
 hipError_t launch_encode(int dtype, const void *A, const void *E, void *P, int R, int Cc, int r, hipStream_t s)
 {
+    if (dtype == 1 && (Cc % 4) == 0) {
+        const int chunks = (Cc + 127) / 128;
+        const long items = (long)R * chunks;
+        hipLaunchKernelGGL(encode_mfma_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, (const bf16_t *)A,
+                           (const bf16_t *)E, (bf16_t *)P, R, Cc, r, chunks);
+        return hipGetLastError();
+    }
     return dtype == 0 ? launch_encode_t<float>(A, E, P, R, Cc, r, s) : launch_encode_t<bf16_t>(A, E, P, R, Cc, r, s);
 }
 
@@ -162,26 +312,39 @@ hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, i
                       : launch_decode_t<bf16_t>(P, Dm, Cmat, R, Cc, r, gelu, s);
 }
 
+static int outer_tiles_per_block(int64_t tiles)
+{
+    // at most 1024 partials; blocks take whole 256-tile steps (4 wavefronts x 64 tiles)
+    int64_t tpb = (tiles + 1023) / 1024;
+    tpb = (tpb + 255) / 256 * 256;
+    return (int)(tpb < 256 ? 256 : tpb);
+}
+
 int outer_reduce_blocks(int64_t tiles)
 {
-    int64_t nb = (tiles + OUTER_TILES_PER_BLOCK - 1) / OUTER_TILES_PER_BLOCK;
-    return (int)nb;
+    const int tpb = outer_tiles_per_block(tiles);
+    return (int)((tiles + tpb - 1) / tpb);
 }
 
 hipError_t launch_outer_reduce(int dtype, const void *P, const void *V, float *G, float *part, int R, int Cc, int r,
                                int accumulate, hipStream_t s)
 {
-    const int nb = outer_reduce_blocks((int64_t)R * Cc);
+    const int64_t tiles = (int64_t)R * Cc;
+    const int tpb = outer_tiles_per_block(tiles);
+    const int nb = outer_reduce_blocks(tiles);
     if (dtype == 0)
         hipLaunchKernelGGL(outer_partial_kernel<float>, dim3(nb), dim3(256), 0, s, (const float *)P, (const float *)V,
-                           part, R, Cc, r, OUTER_TILES_PER_BLOCK);
+                           part, R, Cc, r, tpb);
+    else if (tiles % 8 == 0)
+        hipLaunchKernelGGL(outer_mfma_kernel, dim3(nb), dim3(256), 0, s, (const bf16_t *)P, (const bf16_t *)V, part, R,
+                           Cc, r, tpb);
     else
         hipLaunchKernelGGL(outer_partial_kernel<bf16_t>, dim3(nb), dim3(256), 0, s, (const bf16_t *)P,
-                           (const bf16_t *)V, part, R, Cc, r, OUTER_TILES_PER_BLOCK);
+                           (const bf16_t *)V, part, R, Cc, r, tpb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int n_out = r * 16;
-    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 255) / 256), dim3(256), 0, s, part, G, nb, n_out, accumulate);
+    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 15) / 16), dim3(256), 0, s, part, G, nb, n_out, accumulate);
     return hipGetLastError();
 }
 

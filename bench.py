@@ -2,7 +2,7 @@
 """Benchmark of the STL hot path on one MI355X.
 
 A step is one pass of the whole hot path -- stl_forward (encode -> plane products -> decode, saving
-Yhat) followed by stl_backward (dX, dWhat, dE_X, dD) -- on the forward+backward workload of the
+Xhat and Yhat) followed by stl_backward (dX, dWhat, dE_X, dD) -- on the forward+backward workload of the
 workload list: bf16, m=8192, k=n=4096, t=4, r=32, inputs resident in HBM.  The same step is timed
 for a dense bf16 GEMM of the same m, k, n (torch.matmul: X.W, dC.W^T, X^T.dC) on the same GPU.
 
@@ -127,13 +127,13 @@ def main():
     ws_b = torch.empty(max(nb, 16), dtype=torch.uint8, device="cuda")
 
     def fwd():
-        stl.stl_forward(prob, X, What, E_X, D, C, Yhat, ws_f, nf, stl.STL_FLAG_AUTO)
+        stl.stl_forward(prob, X, What, E_X, D, C, Xhat, Yhat, ws_f, nf, stl.STL_FLAG_AUTO)
 
     def fwd_nosave():
-        stl.stl_forward(prob, X, What, E_X, D, C, None, ws_f, nf, stl.STL_FLAG_AUTO)
+        stl.stl_forward(prob, X, What, E_X, D, C, None, None, ws_f, nf, stl.STL_FLAG_AUTO)
 
     def bwd():
-        stl.stl_backward(prob, X, What, E_X, D, dC, Yhat, dX, dWhat, dE_X, dD, 0, ws_b, nb)
+        stl.stl_backward(prob, X, What, E_X, D, dC, Xhat, Yhat, dX, dWhat, dE_X, dD, 0, ws_b, nb)
 
     def step():
         fwd()
@@ -226,7 +226,7 @@ def main():
             Cs = torch.empty((8192, 4096), dtype=bf, device="cuda")
             nbs = stl.stl_workspace_bytes(pr, stl.STL_OP_FORWARD, 0)
             wss = torch.empty(nbs, dtype=torch.uint8, device="cuda")
-            ms = T.wall(lambda: stl.stl_forward(pr, Xs, Ws, Es, Ds, Cs, None, wss, nbs, 0), S, W)
+            ms = T.wall(lambda: stl.stl_forward(pr, Xs, Ws, Es, Ds, Cs, None, None, wss, nbs, 0), S, W)
             sweep[str(rr)] = round(ms, 5)
             log(f"  sweep r={rr}: forward {ms:.4f} ms")
             del Xs, Ws, Es, Ds, Cs, wss

@@ -86,12 +86,14 @@ stl_status_t stl_encode_weight(const stl_problem_t *prob, const void *W, const v
 /*
  * Forward C = X <> W (Definition 3.1 / Eq. (2); Algorithm 1).
  * X: m x k (in).  What: r x K x N (in).  E_X, D: r x 16 (in).  C: m x n (out).
+ * Xhat_save: NULL, or r x M x K (out, storage dtype): the encoded activations of step (i) are
+ *   written there instead of into the workspace, for stl_backward.
  * Yhat_save: NULL, or r x M x N (out, storage dtype): the encoded output
  *   Yhat[p] = Xhat[p] * What[p] (Claim 3.4) is also written there, for stl_backward.
  * ws / ws_bytes: scratch of at least stl_workspace_bytes(prob, STL_OP_FORWARD, flags).
  */
 stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *What,
-                         const void *E_X, const void *D, void *C, void *Yhat_save,
+                         const void *E_X, const void *D, void *C, void *Xhat_save, void *Yhat_save,
                          void *ws, size_t ws_bytes, int flags, void *stream);
 
 /*
@@ -100,15 +102,16 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
  *   dYhat[p][I][J] = sum_q D[p][q] dc[I][J][q]          dD[p][q]   = sum_{I,J} Yhat[p][I][J] dc[I][J][q]
  *   dXhat[p] = dYhat[p] * What[p]^T                     dWhat[p]   = Xhat[p]^T * dYhat[p]
  *   dx[I][L][q] = sum_p E_X[p][q] dXhat[p][I][L]        dE_X[p][q] = sum_{I,L} dXhat[p][I][L] x[I][L][q]
- * dC: m x n (in).  Yhat_saved: NULL (Yhat is recomputed) or what stl_forward wrote to Yhat_save.
+ * dC: m x n (in).  Xhat_saved / Yhat_saved: NULL (recomputed here) or what stl_forward wrote to
+ *   Xhat_save / Yhat_save for the same X, What, E_X.
  * dX: m x k (out, storage dtype).  dWhat: r x K x N, dE_X, dD: r x 16 (out, fp32).
  * Any of the four outputs may be NULL to skip it.
  * accumulate: 0 overwrites dWhat/dE_X/dD; 1 adds into them (fp32 gradient accumulation).
  * Results are bitwise reproducible run to run (no floating-point atomics).
  */
 stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *What,
-                          const void *E_X, const void *D, const void *dC, const void *Yhat_saved,
-                          void *dX, float *dWhat, float *dE_X, float *dD, int accumulate,
+                          const void *E_X, const void *D, const void *dC, const void *Xhat_saved,
+                          const void *Yhat_saved, void *dX, float *dWhat, float *dE_X, float *dD, int accumulate,
                           void *ws, size_t ws_bytes, void *stream);
 
 /*

@@ -68,8 +68,8 @@ def _load():
     lib.stl_workspace_bytes.restype = ctypes.c_size_t
     lib.stl_workspace_bytes.argtypes = [pp, ctypes.c_int, ctypes.c_int]
     lib.stl_encode_weight.argtypes = [pp, _P, _P, _P, _P]
-    lib.stl_forward.argtypes = [pp, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, ctypes.c_int, _P]
-    lib.stl_backward.argtypes = [pp, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_int, _P, ctypes.c_size_t, _P]
+    lib.stl_forward.argtypes = [pp, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, ctypes.c_int, _P]
+    lib.stl_backward.argtypes = [pp, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_int, _P, ctypes.c_size_t, _P]
     lib.stl_encode_activation.argtypes = [pp, _P, _P, _P, _P]
     lib.stl_plane_matmul.argtypes = [pp, _P, _P, _P, _P]
     lib.stl_decode.argtypes = [pp, _P, _P, _P, ctypes.c_int, _P]
@@ -132,16 +132,16 @@ def stl_encode_weight(prob: Problem, W, E_W, What, stream=None) -> None:
     _check(_load().stl_encode_weight(ctypes.byref(prob.c()), _ptr(W), _ptr(E_W), _ptr(What), _stream(stream)))
 
 
-def stl_forward(prob: Problem, X, What, E_X, D, C, Yhat_save=None, ws=None, ws_bytes: int = 0,
+def stl_forward(prob: Problem, X, What, E_X, D, C, Xhat_save=None, Yhat_save=None, ws=None, ws_bytes: int = 0,
                 flags: int = STL_FLAG_AUTO, stream=None) -> None:
     _check(_load().stl_forward(ctypes.byref(prob.c()), _ptr(X), _ptr(What), _ptr(E_X), _ptr(D), _ptr(C),
-                               _ptr(Yhat_save), _ptr(ws), ws_bytes, flags, _stream(stream)))
+                               _ptr(Xhat_save), _ptr(Yhat_save), _ptr(ws), ws_bytes, flags, _stream(stream)))
 
 
-def stl_backward(prob: Problem, X, What, E_X, D, dC, Yhat_saved, dX, dWhat, dE_X, dD, accumulate: int = 0,
-                 ws=None, ws_bytes: int = 0, stream=None) -> None:
+def stl_backward(prob: Problem, X, What, E_X, D, dC, Xhat_saved, Yhat_saved, dX, dWhat, dE_X, dD,
+                 accumulate: int = 0, ws=None, ws_bytes: int = 0, stream=None) -> None:
     _check(_load().stl_backward(ctypes.byref(prob.c()), _ptr(X), _ptr(What), _ptr(E_X), _ptr(D), _ptr(dC),
-                                _ptr(Yhat_saved), _ptr(dX), _ptr(dWhat), _ptr(dE_X), _ptr(dD), accumulate,
+                                _ptr(Xhat_saved), _ptr(Yhat_saved), _ptr(dX), _ptr(dWhat), _ptr(dE_X), _ptr(dD), accumulate,
                                 _ptr(ws), ws_bytes, _stream(stream)))
 
 

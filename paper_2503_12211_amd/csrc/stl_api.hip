@@ -197,7 +197,7 @@ stl_status_t stl_decode(const stl_problem_t *prob, const void *Yhat, const void 
 }
 
 stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *What, const void *E_X, const void *D,
-                         void *C, void *Yhat_save, void *ws, size_t ws_bytes, int flags, void *stream)
+                         void *C, void *Xhat_save, void *Yhat_save, void *ws, size_t ws_bytes, int flags, void *stream)
 {
     Dims d;
     stl_status_t st = check_problem(prob, &d);
@@ -216,7 +216,7 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
     const bool gelu = (flags & STL_FLAG_GELU) != 0;
     char *base = (char *)ws;
 
-    void *xhat = base + w.xhat;
+    void *xhat = Xhat_save ? Xhat_save : (void *)(base + w.xhat);
     void *yhat = Yhat_save ? Yhat_save : (void *)(base + w.yhat);
     STL_HIP(stl::launch_encode(prob->dtype, X, E_X, xhat, d.M, d.K, d.r, s), "forward/encode");
     stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false};
@@ -226,7 +226,7 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
 }
 
 stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *What, const void *E_X, const void *D,
-                          const void *dC, const void *Yhat_saved, void *dX, float *dWhat, float *dE_X, float *dD,
+                          const void *dC, const void *Xhat_saved, const void *Yhat_saved, void *dX, float *dWhat, float *dE_X, float *dD,
                           int accumulate, void *ws, size_t ws_bytes, void *stream)
 {
     Dims d;
@@ -241,11 +241,13 @@ stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *
     hipStream_t s = (hipStream_t)stream;
     const int dt = prob->dtype;
     char *base = (char *)ws;
-    void *xhat = base + w.xhat, *dyhat = base + w.dyhat, *dxhat = base + w.dxhat;
+    const void *xhat = Xhat_saved ? Xhat_saved : (const void *)(base + w.xhat);
+    void *dyhat = base + w.dyhat, *dxhat = base + w.dxhat;
     float *part = (float *)(base + w.part);
 
     const bool need_xhat = dWhat || (dD && !Yhat_saved);
-    if (need_xhat) STL_HIP(stl::launch_encode(dt, X, E_X, xhat, d.M, d.K, d.r, s), "backward/encode X");
+    if (need_xhat && !Xhat_saved)
+        STL_HIP(stl::launch_encode(dt, X, E_X, base + w.xhat, d.M, d.K, d.r, s), "backward/encode X");
     STL_HIP(stl::launch_encode(dt, dC, D, dyhat, d.M, d.N, d.r, s), "backward/encode dC");
     if (dD) {
         const void *yhat = Yhat_saved;

@@ -1,0 +1,342 @@
+// Pipelined batched plane products on the CDNA4 matrix cores (step (ii) of Algorithm 1, Claim 3.4):
+//     Out[p][i][j] (+)= sum_l A[p](i,l) * B[p](l,j)       bf16 x bf16 -> fp32, p < r planes.
+//
+// Same blocking as the register-staged kernel (256 x 256 block of one plane per workgroup, eight
+// wavefronts of 128 x 64, 32x32x16 MFMA), but HBM -> LDS goes through the LDS-DMA path
+// (global_load_lds, 16 bytes per lane, no VGPR staging) into a ring of NS stages of 32 contraction
+// elements each, issued NS-1 stages ahead of their use, so that an L2 / HBM miss has several
+// MFMA stages of time to land.  Operands keep their memory orientation in LDS:
+//   * contraction-contiguous operand ([row][l]): 64-byte LDS rows, fragments by ds_read_b128;
+//   * contraction-major operand ([l][row]):      512-byte LDS rows, fragments by the transposing
+//     ds_read_b64_tr_b16 (a 16-lane group turns 4 l-rows x 16 columns into 4 consecutive l per lane).
+// An LDS-DMA instruction writes 64 lanes x 16 bytes contiguously, so bank swizzles are applied by
+// permuting which global 16-byte chunk each lane fetches.
+#include "stl_kernels.h"
+#include "stl_device.h"
+
+#include <cstdlib>
+
+namespace stl {
+
+namespace pipe {
+
+constexpr int BKS = 32;                 // contraction elements per stage
+constexpr int OPER_BYTES = 256 * BKS * 2;  // one operand, one stage: 16 KB
+constexpr int STAGE_BYTES = 2 * OPER_BYTES;
+
+typedef short v4i16_t __attribute__((ext_vector_type(4)));
+#define STL_LDS(p) ((__attribute__((address_space(3))) char *)(p))
+
+// swizzles (16-byte chunk index XOR), chosen so that one access phase touches every bank once
+template <int SHIFT>
+__device__ __forceinline__ int fswz(int row) { return (row >> SHIFT) & 3; }     // [row][l] operand, 4 chunks per row
+__device__ __forceinline__ int gswz(int k) { return (k & 3) << 2; }              // [l][row] operand, 32 chunks per row
+
+// LDS-DMA load, 16 bytes per lane: lane L's bytes land at lds_wave_base + 16*L (M0 carries the wave-uniform LDS
+// address).  Issued as inline assembly on purpose: the main loop orders these loads against the fragment reads
+// itself (vmcnt + barrier below); letting the compiler track them makes it drain every outstanding load before
+// each LDS read, which removes the prefetch distance this kernel exists for.
+__device__ __forceinline__ void dma16(const bf16_t *g, uint32_t lds_wave_base)
+{
+    const uint32_t l = __builtin_amdgcn_readfirstlane(lds_wave_base);
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(l) : "memory", "m0");
+}
+
+__device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// Per-thread global source pointers for the two DMA instructions a wavefront issues per operand and stage.
+template <bool KMAJOR, int SWZ>
+struct Src {
+    const bf16_t *p[2];
+    long step;  // elements to advance per stage
+    __device__ __forceinline__ void init(const bf16_t *base, long ld, int row0, int rows_total, int wave, int lane)
+    {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int q = 2 * wave + j;
+            if (!KMAJOR) {
+                const int row = 16 * q + (lane >> 2), c = (lane & 3) ^ fswz<SWZ>(row);
+                int gr = row0 + row;
+                gr = gr < rows_total ? gr : rows_total - 1;   // rows past the edge feed only discarded outputs
+                p[j] = base + (size_t)gr * ld + 8 * c;
+            } else {
+                const int k = 2 * q + (lane >> 5), nc = (lane & 31) ^ gswz(k);
+                int gc = row0 + 8 * nc;
+                gc = gc < rows_total ? gc : rows_total - 8;
+                p[j] = base + (size_t)k * ld + gc;
+            }
+        }
+        step = KMAJOR ? (long)BKS * ld : BKS;
+    }
+    __device__ __forceinline__ void issue(uint32_t oper_stage, int wave)   // LDS byte address of the operand stage
+    {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            dma16(p[j], oper_stage + (2 * wave + j) * 1024);
+            p[j] += step;
+        }
+    }
+};
+
+// Fragment addressing: byte offset inside one operand stage for MFMA rows (frag_row0 + lane%32), k16-step ks.
+template <bool KMAJOR, int SWZ>
+struct Frag {
+    int off[2][2];   // [ks][kk]; kk only used for the transposing form
+    __device__ __forceinline__ void init(int tile_row0, int lane)
+    {
+        const int h = lane >> 5;
+        if (!KMAJOR) {
+            const int row = tile_row0 + (lane & 31);
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                off[ks][0] = row * 64 + (((2 * ks + h) ^ fswz<SWZ>(row)) << 4);
+                off[ks][1] = 0;
+            }
+        } else {
+            const int i = lane & 15, blk = (lane >> 4) & 1;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) {
+                    const int k = 16 * ks + 8 * h + 4 * kk + (i >> 2);
+                    const int col = tile_row0 + 16 * blk + 4 * (i & 3);
+                    off[ks][kk] = k * 512 + (((col >> 3) ^ gswz(k)) << 4) + ((col & 7) << 1);
+                }
+        }
+    }
+    // fragment f (32 rows further per f) of k16-step ks
+    __device__ __forceinline__ bf16x8_t read(const char *oper_stage, int f, int ks) const
+    {
+        if (!KMAJOR) {
+            return *reinterpret_cast<const bf16x8_t *>(oper_stage + off[ks][0] + f * 32 * 64);
+        } else {
+            // Fragment f starts 32 columns = 4 chunks further.  The wavefront's first column is a multiple of
+            // 64, so chunk bits 2..3 of this lane's column are free and "+4f" is "^ (f<<2)", which commutes with
+            // the swizzle XOR: in bytes, off ^ (f << 6).
+            const v4i16_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) v4i16_t *)STL_LDS(oper_stage + (off[ks][0] ^ (f << 6))));
+            const v4i16_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) v4i16_t *)STL_LDS(oper_stage + (off[ks][1] ^ (f << 6))));
+            struct { v4i16_t a, b; } both = {lo, hi};
+            return __builtin_bit_cast(bf16x8_t, both);
+        }
+    }
+};
+
+// Instruction order inside one k16-step: the first MFMA (whose operands were fetched a whole step ago), then all
+// LDS reads of the following step, then the remaining MFMAs -- so that no LDS latency sits in front of an MFMA.
+#define STL_ORDER_MFMA_READS()                                  \
+    do {                                                        \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);     \
+        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);      \
+    } while (0)
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    else static_assert(N == 0, "unsupported vmcnt");
+}
+
+}  // namespace pipe
+
+// A_T: A stored [l][i];  B_T: B stored [l][j].  Requires Kl % 32 == 0, Mi % 8 == 0, Nj % 8 == 0.
+template <int NS, int SWZ, bool A_T, bool B_T, typename TO, bool ACC>
+__global__ __launch_bounds__(512) void gemm_pipe_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B,
+                                                        TO *__restrict__ Out, int Mi, int Nj, int Kl, int tiles_m,
+                                                        int tiles_n, int total)
+{
+    using namespace pipe;
+    constexpr int BM = 256, BN = 256, WAVES_N = 4, WM = 128, WN = 64, FM = 4, FN = 2;
+    extern __shared__ __align__(16) char smem[];
+
+    int bid = blockIdx.x;
+    if ((total & 7) == 0) bid = (bid & 7) * (total >> 3) + (bid >> 3);   // consecutive blocks of a plane on one XCD
+    const int per_plane = tiles_m * tiles_n;
+    const int p = bid / per_plane;
+    const int rem = bid - p * per_plane;
+    const int i0 = (rem / tiles_n) * BM, j0 = (rem % tiles_n) * BN;
+
+    A += (size_t)p * Mi * Kl;
+    B += (size_t)p * Kl * Nj;
+    Out += (size_t)p * Mi * Nj;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+    Src<A_T, SWZ> sa;
+    Src<B_T, SWZ> sb;
+    sa.init(A, A_T ? Mi : Kl, i0, Mi, wave, lane);
+    sb.init(B, B_T ? Nj : Kl, j0, Nj, wave, lane);
+    Frag<A_T, SWZ> fa;
+    Frag<B_T, SWZ> fb;
+    fa.init(wm * WM, lane);
+    fb.init(wn * WN, lane);
+
+    f32x16_t acc[FM][FN];
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int b = 0; b < FN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    const int nks = Kl / BKS;
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)STL_LDS(smem);
+    static_assert(NS == 4 || NS == 3, "ring depth");
+    // Each wavefront issues 4 DMA instructions per stage.  Stage s+NS-1 is issued in iteration s, stage s+1 must
+    // have landed at the top of iteration s (fragments are fetched one k16-step ahead, across the stage
+    // boundary), so NS-3 later stages may still be in flight there.
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) {
+        if (s < nks) {
+            sa.issue(smem_lds + s * STAGE_BYTES, wave);
+            sb.issue(smem_lds + s * STAGE_BYTES + OPER_BYTES, wave);
+        }
+    }
+    if (nks > NS - 2) wait_vmcnt<4 * (NS - 2)>();
+    else wait_vmcnt<0>();
+    block_barrier();
+
+    bf16x8_t va[2][FM], vb[2][FN];      // fragment double buffer: [k16-step parity]
+#pragma unroll
+    for (int a = 0; a < FM; ++a) va[0][a] = fa.read(smem, a, 0);
+#pragma unroll
+    for (int b = 0; b < FN; ++b) vb[0][b] = fb.read(smem + OPER_BYTES, b, 0);
+
+    for (int s = 0; s < nks; ++s) {
+        if (s + 1 < nks) {
+            if (s + NS - 2 < nks) wait_vmcnt<4 * (NS - 3)>();
+            else wait_vmcnt<0>();
+        }
+        block_barrier();                 // stage s+1 visible to all; nobody reads stage s-1 any more
+        if (s + NS - 1 < nks) {
+            const uint32_t dst = smem_lds + ((s + NS - 1) % NS) * STAGE_BYTES;
+            sa.issue(dst, wave);
+            sb.issue(dst + OPER_BYTES, wave);
+        }
+        const char *cur = smem + (s % NS) * STAGE_BYTES;
+        const char *nxt = smem + ((s + 1) % NS) * STAGE_BYTES;
+        // k16-step 0 of stage s runs on fragments fetched during the previous step, while step 1's fragments
+        // are fetched; then step 1 runs while step 0 of stage s+1 is fetched.  The scheduling fences keep the
+        // compiler from folding the two register sets back into one (which serialises LDS latency and MFMA).
+#pragma unroll
+        for (int a = 0; a < FM; ++a) va[1][a] = fa.read(cur, a, 1);
+#pragma unroll
+        for (int b = 0; b < FN; ++b) vb[1][b] = fb.read(cur + OPER_BYTES, b, 1);
+#pragma unroll
+        for (int a = 0; a < FM; ++a)
+#pragma unroll
+            for (int b = 0; b < FN; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[0][a], vb[0][b], acc[a][b], 0, 0, 0);
+        STL_ORDER_MFMA_READS();
+        __builtin_amdgcn_sched_barrier(0);
+        // (unconditional: after the last stage this reads a stale ring slot whose values are never used;
+        //  a branch here would make the compiler drain all LDS reads before the MFMAs below)
+#pragma unroll
+        for (int a = 0; a < FM; ++a) va[0][a] = fa.read(nxt, a, 0);
+#pragma unroll
+        for (int b = 0; b < FN; ++b) vb[0][b] = fb.read(nxt + OPER_BYTES, b, 0);
+#pragma unroll
+        for (int a = 0; a < FM; ++a)
+#pragma unroll
+            for (int b = 0; b < FN; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][a], vb[1][b], acc[a][b], 0, 0, 0);
+        STL_ORDER_MFMA_READS();
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // Epilogue: 32 rows x WN columns per wavefront at a time through LDS, 16-byte row-contiguous stores.
+    // Accumulator layout of a 32x32 fragment: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4.
+    constexpr int ES = sizeof(TO);
+    constexpr int PITCH = WN * ES + 16;
+    constexpr int LPR = WN * ES / 16;
+    constexpr int RPI = 64 / LPR;
+    char *slab = smem + wave * (32 * PITCH);
+    const int frow = lane & 31, fhalf = lane >> 5;
+#pragma unroll
+    for (int a = 0; a < FM; ++a) {
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < FN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rr = 8 * (v >> 2) + 4 * fhalf + (v & 3), cc = b * 32 + frow;
+                Elem<TO>::st(reinterpret_cast<TO *>(slab + rr * PITCH) + cc, acc[a][b][v]);
+            }
+        __syncthreads();
+        const int gi_base = i0 + wm * WM + a * 32;
+        const int gj = j0 + wn * WN + (lane % LPR) * (16 / ES);
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int rr = it * RPI + lane / LPR;
+            const int gi = gi_base + rr;
+            if (gi < Mi && gj < Nj) {
+                u32x4_t w = *reinterpret_cast<const u32x4_t *>(slab + rr * PITCH + (lane % LPR) * 16);
+                TO *o = Out + (size_t)gi * Nj + gj;
+                if (ACC) {
+                    const f32x4_t old = *reinterpret_cast<const f32x4_t *>(o);
+                    f32x4_t nw = __builtin_bit_cast(f32x4_t, w);
+                    nw += old;
+                    *reinterpret_cast<f32x4_t *>(o) = nw;
+                } else {
+                    *reinterpret_cast<u32x4_t *>(o) = w;
+                }
+            }
+        }
+    }
+}
+
+bool plane_gemm_pipe_eligible(const GemmDesc &g)
+{
+    if (!plane_gemm_mfma_eligible(g)) return false;
+    if (g.Kl % pipe::BKS) return false;
+    // a clamped edge chunk must still lie inside the operand
+    if (g.Mi < 8 || g.Nj < 8) return false;
+    return g.Mi > 128 && g.Nj > 128;
+}
+
+template <int NS, int SWZ, bool A_T, bool B_T, typename TO, bool ACC>
+static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
+{
+    auto kern = gemm_pipe_kernel<NS, SWZ, A_T, B_T, TO, ACC>;
+    constexpr int smem = NS * pipe::STAGE_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles_m = (g.Mi + 255) / 256, tiles_n = (g.Nj + 255) / 256;
+    const long total = (long)tiles_m * tiles_n * g.batch;
+    if (total > 0x7fffffffL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(512), smem, s, (const bf16_t *)A, (const bf16_t *)B, (TO *)Out,
+                       g.Mi, g.Nj, g.Kl, tiles_m, tiles_n, (int)total);
+    return hipGetLastError();
+}
+
+template <int NS, int SWZ>
+static hipError_t launch_pipe_form(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
+{
+    if (g.out_f32) {
+        return g.accumulate ? launch_pipe_cfg<NS, SWZ, true, true, float, true>(g, A, B, Out, s)
+                            : launch_pipe_cfg<NS, SWZ, true, true, float, false>(g, A, B, Out, s);
+    }
+    if (g.b_kmajor) return launch_pipe_cfg<NS, SWZ, false, true, bf16_t, false>(g, A, B, Out, s);
+    return launch_pipe_cfg<NS, SWZ, false, false, bf16_t, false>(g, A, B, Out, s);
+}
+
+hipError_t launch_plane_gemm_pipe(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
+{
+    static const int swz = []() { const char *e = getenv("STL_GEMM_SWZ"); return e ? atoi(e) : 1; }();
+    static const int ns = []() { const char *e = getenv("STL_GEMM_NS"); return e ? atoi(e) : 4; }();
+    if (ns == 3) return swz == 2 ? launch_pipe_form<3, 2>(g, A, B, Out, s) : launch_pipe_form<3, 1>(g, A, B, Out, s);
+    return swz == 2 ? launch_pipe_form<4, 2>(g, A, B, Out, s) : launch_pipe_form<4, 1>(g, A, B, Out, s);
+}
+
+}  // namespace stl

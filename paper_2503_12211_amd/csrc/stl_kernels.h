@@ -34,5 +34,8 @@ hipError_t launch_plane_gemm_generic(int dtype, const GemmDesc &g, const void *A
 // bf16 MFMA path; returns false in *ok if the shape is not eligible (caller falls back)
 bool plane_gemm_mfma_eligible(const GemmDesc &g);
 hipError_t launch_plane_gemm_mfma(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s);
+// bf16 MFMA path with LDS-DMA loads and a multi-stage LDS ring (large planes, contraction % 32 == 0)
+bool plane_gemm_pipe_eligible(const GemmDesc &g);
+hipError_t launch_plane_gemm_pipe(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s);
 
 }  // namespace stl

@@ -126,6 +126,7 @@ __global__ __launch_bounds__(256) void outer_final_kernel(const float *__restric
     const int i = blockIdx.x * 16 + o;
     float s = 0.f;
     if (i < n_out)
+#pragma unroll 8
         for (int b = sl; b < nblocks; b += 16) s += part[(size_t)b * n_out + i];
     red[sl][o] = s;
     __syncthreads();
@@ -271,6 +272,100 @@ __global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restric
 }
 
 // ---------------------------------------------------------------------------------------
+// bf16 decode on the matrix cores:  tile entries (16) x tiles = D^T (16 x r) . Yhat (r x tiles),
+// v_mfma_f32_16x16x32_bf16 with rows = tile entries, columns = 16 tiles, K = planes.
+// A wavefront takes 64 consecutive tiles of one tile row: the r plane segments (128 bytes each) are
+// read coalesced into a private LDS slab [plane][tile]; the transposing ds_read_b64_tr_b16 hands
+// every lane 4 consecutive planes of its tile (the MFMA B fragment).  The accumulator leaves each
+// lane with one row of one output tile (4 entries = 8 bytes), so 16 lanes store 128 contiguous bytes.
+// ---------------------------------------------------------------------------------------
+typedef short v4i16_t __attribute__((ext_vector_type(4)));
+
+template <bool GELU, int KC>   // KC = number of 32-plane groups (1: r <= 32, 2: r <= 64)
+__global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restrict__ P, const bf16_t *__restrict__ Dm,
+                                                          bf16_t *__restrict__ Cmat, int R, int Cc, int r, int chunks)
+{
+    constexpr int ROWB = 128;                               // bytes per LDS row (64 tiles)
+    __shared__ __align__(16) char slab_all[4][KC * 32 * ROWB];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    char *slab = slab_all[wave];
+    const int j = lane & 15, kq = lane >> 4;
+
+    // A fragments: lane (entry q = j, kq) holds D[32g + 8kq + e][q], e = 0..7
+    bf16x8_t fa[KC];
+#pragma unroll
+    for (int g = 0; g < KC; ++g) {
+        uint32_t w[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            const int p0 = 32 * g + 8 * kq + 2 * e2;
+            const uint32_t lo = p0 < r ? Dm[p0 * 16 + j] : 0u, hi = p0 + 1 < r ? Dm[(p0 + 1) * 16 + j] : 0u;
+            w[e2] = lo | (hi << 16);
+        }
+        fa[g] = __builtin_bit_cast(bf16x8_t, u32x4_t{w[0], w[1], w[2], w[3]});
+    }
+    // rows of planes >= r are never loaded: keep them zero (they meet zero A entries, but must be finite)
+    for (int i = lane; i < KC * 32 * ROWB / 16; i += 64) reinterpret_cast<u32x4_t *>(slab)[i] = u32x4_t{0u, 0u, 0u, 0u};
+
+    // swizzle of the 16-byte chunk index inside a row, so that the 8 plane rows one transposing read touches
+    // (planes 0-3 and 8-11, or 4-7 and 12-15, of a 16-tile column group) fall into different bank windows
+    auto swz = [](int row) { return ((((row >> 1) & 1) | (((row >> 3) & 1) << 1)) << 1); };
+
+    const size_t plane = (size_t)R * Cc;
+    const size_t ld = (size_t)Cc * 4;
+    const long items = (long)R * chunks;
+    for (long item0 = (long)blockIdx.x * 4; item0 < items; item0 += (long)gridDim.x * 4) {
+        const long item = item0 + wave;
+        const bool live = item < items;
+        const int I = live ? (int)(item / chunks) : 0, J0 = live ? (int)(item % chunks) * 64 : 0;
+        __syncthreads();                                    // previous round's fragment reads are done
+        if (live) {
+            // lane -> (plane within group of 8, 16-byte chunk = 8 tiles)
+            const int pr = lane >> 3, ch = lane & 7;
+            const int Jl = J0 + 8 * ch;
+#pragma unroll
+            for (int g8 = 0; g8 < KC * 4; ++g8) {
+                const int pl = 8 * g8 + pr;
+                if (pl < r && Jl < Cc) {
+                    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(P + (size_t)pl * plane + (size_t)I * Cc + Jl);
+                    *reinterpret_cast<u32x4_t *>(slab + pl * ROWB + ((ch ^ swz(pl)) << 4)) = v;
+                }
+            }
+        }
+        __syncthreads();
+        if (live) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {                   // 16 tiles per MFMA
+                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int g = 0; g < KC; ++g) {
+                    v4i16_t t[2];
+#pragma unroll
+                    for (int kk = 0; kk < 2; ++kk) {
+                        // source row for this lane of the 16-lane group: plane 32g + 8kq + 4kk + j/4, tiles 16u + 4(j%4)
+                        const int row = 32 * g + 8 * kq + 4 * kk + (j >> 2);
+                        const int col = 16 * u + 4 * (j & 3);
+                        const char *src = slab + row * ROWB + ((((col >> 3)) ^ swz(row)) << 4) + ((col & 7) << 1);
+                        t[kk] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t *)(
+                            (__attribute__((address_space(3))) char *)src));
+                    }
+                    struct { v4i16_t a, b; } both = {t[0], t[1]};
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[g], __builtin_bit_cast(bf16x8_t, both), acc, 0, 0, 0);
+                }
+                // lane holds row a = kq of tile J0 + 16u + j: entries acc[0..3]
+                const int J = J0 + 16 * u + j;
+                if (J < Cc) {
+                    float c0 = acc[0], c1 = acc[1], c2 = acc[2], c3 = acc[3];
+                    if (GELU) { c0 = gelu_erf(c0); c1 = gelu_erf(c1); c2 = gelu_erf(c2); c3 = gelu_erf(c3); }
+                    const u32x2_t w = {pack_bf16x2(c0, c1), pack_bf16x2(c2, c3)};
+                    *reinterpret_cast<u32x2_t *>(Cmat + ((size_t)I * 4 + kq) * ld + (size_t)J * 4) = w;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------------------
 template <typename T>
@@ -308,14 +403,31 @@ static hipError_t launch_decode_t(const void *P, const void *Dm, void *Cmat, int
 hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, int R, int Cc, int r, bool gelu,
                          hipStream_t s)
 {
+    if (dtype == 1 && (Cc % 8) == 0) {
+        const int chunks = (Cc + 63) / 64;
+        const long items = (long)R * chunks;
+        long blocks = (items + 3) / 4;
+        if (blocks > 8192) blocks = 8192;                   // grid-stride over (tile row, 64-tile chunk) items
+        const dim3 grid((unsigned)blocks), block(256);
+        const bf16_t *p = (const bf16_t *)P, *d = (const bf16_t *)Dm;
+        bf16_t *c = (bf16_t *)Cmat;
+        if (r <= 32) {
+            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 1>), grid, block, 0, s, p, d, c, R, Cc, r, chunks);
+            else hipLaunchKernelGGL((decode_mfma_kernel<false, 1>), grid, block, 0, s, p, d, c, R, Cc, r, chunks);
+        } else {
+            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 2>), grid, block, 0, s, p, d, c, R, Cc, r, chunks);
+            else hipLaunchKernelGGL((decode_mfma_kernel<false, 2>), grid, block, 0, s, p, d, c, R, Cc, r, chunks);
+        }
+        return hipGetLastError();
+    }
     return dtype == 0 ? launch_decode_t<float>(P, Dm, Cmat, R, Cc, r, gelu, s)
                       : launch_decode_t<bf16_t>(P, Dm, Cmat, R, Cc, r, gelu, s);
 }
 
 static int outer_tiles_per_block(int64_t tiles)
 {
-    // at most 1024 partials; blocks take whole 256-tile steps (4 wavefronts x 64 tiles)
-    int64_t tpb = (tiles + 1023) / 1024;
+    // at most 512 partials; blocks take whole 256-tile steps (4 wavefronts x 64 tiles)
+    int64_t tpb = (tiles + 511) / 512;
     tpb = (tpb + 255) / 256 * 256;
     return (int)(tpb < 256 ? 256 : tpb);
 }

@@ -29,7 +29,7 @@ def workspace(prob, op, flags=0):
     return torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda"), nbytes
 
 
-def forward(p, dtype, flags=0, save_yhat=False):
+def forward(p, dtype, flags=0, save_yhat=False, save_xhat=False):
     """p: dict with X, What, E_X, D (numpy).  Returns C (and Yhat) as float64 numpy."""
     m, k = p["X"].shape
     r, K, N = p["What"].shape
@@ -38,19 +38,23 @@ def forward(p, dtype, flags=0, save_yhat=False):
     X, What, E_X, D = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D"))
     C = torch.full((m, n), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
     Y = torch.full((r, m // 4, N), float("nan"), dtype=TORCH_DT[dtype], device="cuda") if save_yhat else None
+    Xh = torch.full((r, m // 4, k // 4), float("nan"), dtype=TORCH_DT[dtype], device="cuda") if save_xhat else None
     ws, nbytes = workspace(prob, stl.STL_OP_FORWARD, flags)
-    stl.stl_forward(prob, X, What, E_X, D, C, Y, ws, nbytes, flags)
+    stl.stl_forward(prob, X, What, E_X, D, C, Xh, Y, ws, nbytes, flags)
     torch.cuda.synchronize()
+    if save_xhat:
+        return host(C), host(Xh), host(Y)
     return (host(C), host(Y)) if save_yhat else host(C)
 
 
-def backward(p, dtype, yhat=None, accumulate=0, init=None, skip=()):
+def backward(p, dtype, yhat=None, accumulate=0, init=None, skip=(), xhat=None):
     m, k = p["X"].shape
     r, K, N = p["What"].shape
     n = 4 * N
     prob = stl.Problem(m, k, n, r, STL_DT[dtype])
     X, What, E_X, D, dC = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D", "dC"))
     Y = dev(yhat, dtype) if yhat is not None else None
+    Xh = dev(xhat, dtype) if xhat is not None else None
     dX = torch.full((m, k), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
     f32 = dict(dtype=torch.float32, device="cuda")
     if init is None:
@@ -62,7 +66,7 @@ def backward(p, dtype, yhat=None, accumulate=0, init=None, skip=()):
     outs = {"dX": dX, "dWhat": dWhat, "dE_X": dE_X, "dD": dD}
     args = {k_: (None if k_ in skip else v) for k_, v in outs.items()}
     ws, nbytes = workspace(prob, stl.STL_OP_BACKWARD)
-    stl.stl_backward(prob, X, What, E_X, D, dC, Y, args["dX"], args["dWhat"], args["dE_X"], args["dD"],
+    stl.stl_backward(prob, X, What, E_X, D, dC, Xh, Y, args["dX"], args["dWhat"], args["dE_X"], args["dD"],
                      accumulate, ws, nbytes)
     torch.cuda.synchronize()
     return {k_: host(v) for k_, v in outs.items()}

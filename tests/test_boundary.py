@@ -35,10 +35,10 @@ def test_invalid_problem_is_rejected(kw, status):
     prob = stl.Problem(**base)
     assert stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD) == 0
     with pytest.raises(stl.StlError) as e:
-        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, 1 << 40, 0, stream=0)
+        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 1 << 40, 0, stream=0)
     assert e.value.status == status
     with pytest.raises(stl.StlError):
-        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, 0, FAKE, 1 << 40, stream=0)
+        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, FAKE, 0, FAKE, 1 << 40, stream=0)
     with pytest.raises(stl.StlError):
         stl.stl_encode_weight(prob, FAKE, FAKE, FAKE, stream=0)
 
@@ -48,26 +48,26 @@ def test_null_pointers_and_workspace():
     need = stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD, stl.STL_FLAG_UNFUSED)
     assert need >= 2 * 32 * 64 * 64 * 2
     with pytest.raises(stl.StlError) as e:
-        stl.stl_forward(prob, None, FAKE, FAKE, FAKE, FAKE, None, FAKE, need, stl.STL_FLAG_UNFUSED, stream=0)
+        stl.stl_forward(prob, None, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, need, stl.STL_FLAG_UNFUSED, stream=0)
     assert e.value.status == 1
     with pytest.raises(stl.StlError) as e:
-        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, need - 1, stl.STL_FLAG_UNFUSED, stream=0)
+        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, need - 1, stl.STL_FLAG_UNFUSED, stream=0)
     assert e.value.status == 3 and "workspace" in str(e.value)
     with pytest.raises(stl.StlError) as e:
-        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, 0, stl.STL_FLAG_UNFUSED, stream=0)
+        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None, 0, stl.STL_FLAG_UNFUSED, stream=0)
     assert e.value.status == 3
     with pytest.raises(stl.StlError) as e:
-        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, need, 0x4000, stream=0)
+        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, need, 0x4000, stream=0)
     assert e.value.status == 2
     bneed = stl.stl_workspace_bytes(prob, stl.STL_OP_BACKWARD)
     with pytest.raises(stl.StlError) as e:
-        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, FAKE, 0, FAKE, bneed, stream=0)
+        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, None, None, None, FAKE, FAKE, FAKE, FAKE, 0, FAKE, bneed, stream=0)
     assert e.value.status == 1
     with pytest.raises(stl.StlError) as e:
-        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, 2, FAKE, bneed, stream=0)
+        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, FAKE, 2, FAKE, bneed, stream=0)
     assert e.value.status == 1
     with pytest.raises(stl.StlError) as e:
-        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, 0, FAKE, bneed - 1, stream=0)
+        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, FAKE, 0, FAKE, bneed - 1, stream=0)
     assert e.value.status == 3
 
 

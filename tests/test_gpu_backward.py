@@ -80,10 +80,12 @@ def test_backward_saved_yhat_accumulate_and_skips(gu):
     dtype = "bf16"
     p = stl_synth.stl_problem(96, 160, 128, 16, seed=61, dtype=dtype, with_dC=True)
     ref = oracle_grads(p)
-    C, Y = gu.forward(p, dtype, save_yhat=True)
+    C, Xh, Y = gu.forward(p, dtype, save_yhat=True, save_xhat=True)
     with_saved = gu.backward(p, dtype, yhat=Y)
+    both_saved = gu.backward(p, dtype, yhat=Y, xhat=Xh)
     for name in NAMES:
         assert gu.rel(with_saved[name], ref[name]) <= gu.TOL[dtype], name
+        assert np.array_equal(with_saved[name], both_saved[name]), name
     rng = np.random.default_rng(2)
     init = [rng.standard_normal(ref[nm].shape).astype(np.float32) for nm in ("dWhat", "dE_X", "dD")]
     acc = gu.backward(p, dtype, accumulate=1, init=init)
@@ -95,9 +97,12 @@ def test_backward_saved_yhat_accumulate_and_skips(gu):
     assert gu.rel(part["dE_X"], ref["dE_X"]) <= gu.TOL[dtype]
 
 
-def test_backward_matrix_core_shapes_bf16(gu):
-    """Plane sizes that take the MFMA kernels in all three products, with ragged blocks."""
-    p = stl_synth.stl_problem(1056, 544, 800, 8, seed=71, dtype="bf16", with_dC=True)
+@pytest.mark.parametrize("shape", [(1056, 544, 800, 8), (1152, 1152, 1152, 3), (1184, 1152, 1216, 2)])
+def test_backward_matrix_core_shapes_bf16(gu, shape):
+    """Plane sizes that take the MFMA kernels (register-staged and LDS-DMA pipelined) in all three
+    products, with blocks that hang over the edge."""
+    m, k, n, r = shape
+    p = stl_synth.stl_problem(m, k, n, r, seed=71 + r, dtype="bf16", with_dC=True)
     got = gu.backward(p, "bf16")
     ref = oracle_grads(p, use_planes=True)
     for name in NAMES:

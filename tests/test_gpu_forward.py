@@ -54,7 +54,7 @@ def test_forward_small_and_ragged(gu, dtype, shape):
 
 MFMA_SHAPES = [  # tile counts are multiples of 8 (matrix-core path), not multiples of the block sizes
     (1056, 544, 800, 5), (512, 1024, 512, 32), (288, 2080, 1312, 16), (2048, 256, 96, 64), (32, 32, 32, 3),
-    (1024, 512, 1056, 49),
+    (1024, 512, 1056, 49), (1152, 1152, 1152, 3), (1184, 1152, 1216, 2),
 ]
 
 

@@ -20,6 +20,10 @@ FLAGS = [
 ]
 
 
+if os.environ.get("STL_GEMM_TIMELINE"):     # development aid: per-block timestamps inside the pipelined GEMM
+    FLAGS.append("-DSTL_GEMM_TIMELINE")
+
+
 def sources():
     return sorted(CSRC.glob("*.hip"))
 

@@ -77,11 +77,10 @@ FwdWs fwd_layout(const Dims &d, int variant)
 {
     FwdWs w{};
     size_t off = 0;
-    (void)variant;
     w.xhat = off;
-    off += align256((size_t)d.r * d.M * d.K * d.es);
+    if (variant != STL_FLAG_FUSED) off += align256((size_t)d.r * d.M * d.K * d.es);
     w.yhat = off;
-    off += align256((size_t)d.r * d.M * d.N * d.es);
+    if (variant == STL_FLAG_AUTO || variant == STL_FLAG_UNFUSED) off += align256((size_t)d.r * d.M * d.N * d.es);
     w.total = off;
     return w;
 }
@@ -206,17 +205,32 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
     st = check_flags(flags, &variant);
     if (st != STL_OK) return st;
     if (!X || !What || !E_X || !D || !C) return fail(STL_ERR_INVALID_ARG, "stl_forward: NULL pointer");
-    if (variant == STL_FLAG_EPILOGUE || variant == STL_FLAG_FUSED)
-        return fail(STL_ERR_UNSUPPORTED, "stl_forward: variant %d is not available in this build", variant);
+    if (variant == STL_FLAG_EPILOGUE || variant == STL_FLAG_FUSED) {
+        if (!stl::block_forward_eligible(prob->dtype, d.M, d.K, d.N, d.r))
+            return fail(STL_ERR_UNSUPPORTED,
+                        "stl_forward: the block-resident variants need bf16 storage, r <= 32, k %% 64 == 0 and n %% 32 == 0");
+        if (variant == STL_FLAG_FUSED && Xhat_save)
+            return fail(STL_ERR_UNSUPPORTED, "stl_forward: the fused variant never materialises Xhat (Xhat_save must be NULL)");
+    }
     const FwdWs w = fwd_layout(d, variant);
     if (w.total > 0 && (!ws || ws_bytes < w.total))
         return fail(STL_ERR_WORKSPACE, "stl_forward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
-    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_forward: workspace is not 16-byte aligned");
+    if (ws && ((uintptr_t)ws & 15)) return fail(STL_ERR_INVALID_ARG, "stl_forward: workspace is not 16-byte aligned");
     hipStream_t s = (hipStream_t)stream;
     const bool gelu = (flags & STL_FLAG_GELU) != 0;
     char *base = (char *)ws;
 
+    if (variant == STL_FLAG_FUSED) {
+        STL_HIP(stl::launch_block_forward(true, X, What, E_X, D, C, Yhat_save, d.M, d.K, d.N, d.r, gelu, s), "forward/fused");
+        return STL_OK;
+    }
     void *xhat = Xhat_save ? Xhat_save : (void *)(base + w.xhat);
+    if (variant == STL_FLAG_EPILOGUE) {
+        STL_HIP(stl::launch_encode(prob->dtype, X, E_X, xhat, d.M, d.K, d.r, s), "forward/encode");
+        STL_HIP(stl::launch_block_forward(false, xhat, What, E_X, D, C, Yhat_save, d.M, d.K, d.N, d.r, gelu, s),
+                "forward/plane products + decode");
+        return STL_OK;
+    }
     void *yhat = Yhat_save ? Yhat_save : (void *)(base + w.yhat);
     STL_HIP(stl::launch_encode(prob->dtype, X, E_X, xhat, d.M, d.K, d.r, s), "forward/encode");
     stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false};

@@ -21,8 +21,6 @@ namespace stl {
 namespace pipe {
 
 constexpr int BKS = 32;                 // contraction elements per stage
-constexpr int OPER_BYTES = 256 * BKS * 2;  // one operand, one stage: 16 KB
-constexpr int STAGE_BYTES = 2 * OPER_BYTES;
 
 typedef short v4i16_t __attribute__((ext_vector_type(4)));
 #define STL_LDS(p) ((__attribute__((address_space(3))) char *)(p))
@@ -44,23 +42,26 @@ __device__ __forceinline__ void dma16(const bf16_t *g, uint32_t lds_wave_base)
 
 __device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
-// Per-thread global source pointers for the two DMA instructions a wavefront issues per operand and stage.
-template <bool KMAJOR, int SWZ>
+// Per-thread global source pointers for the DMA instructions a wavefront issues per operand and stage.
+// One operand stage is ROWS x 32 contraction elements = ROWS/16 KB = ROWS/16 instructions, dealt to NW wavefronts.
+template <bool KMAJOR, int SWZ, int ROWS, int NW>
 struct Src {
-    const bf16_t *p[2];
+    static constexpr int NI = ROWS / 16 / NW;          // instructions per wavefront
+    static constexpr int CPR = ROWS / 8;               // 16-byte chunks per LDS row of the [l][row] form
+    const bf16_t *p[NI];
     long step;  // elements to advance per stage
     __device__ __forceinline__ void init(const bf16_t *base, long ld, int row0, int rows_total, int wave, int lane)
     {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int q = 2 * wave + j;
+        for (int j = 0; j < NI; ++j) {
+            const int q = NI * wave + j;
             if (!KMAJOR) {
                 const int row = 16 * q + (lane >> 2), c = (lane & 3) ^ fswz<SWZ>(row);
                 int gr = row0 + row;
                 gr = gr < rows_total ? gr : rows_total - 1;   // rows past the edge feed only discarded outputs
                 p[j] = base + (size_t)gr * ld + 8 * c;
             } else {
-                const int k = 2 * q + (lane >> 5), nc = (lane & 31) ^ gswz(k);
+                const int k = (64 / CPR) * q + lane / CPR, nc = (lane % CPR) ^ gswz(k);
                 int gc = row0 + 8 * nc;
                 gc = gc < rows_total ? gc : rows_total - 8;
                 p[j] = base + (size_t)k * ld + gc;
@@ -71,15 +72,15 @@ struct Src {
     __device__ __forceinline__ void issue(uint32_t oper_stage, int wave)   // LDS byte address of the operand stage
     {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            dma16(p[j], oper_stage + (2 * wave + j) * 1024);
+        for (int j = 0; j < NI; ++j) {
+            dma16(p[j], oper_stage + (NI * wave + j) * 1024);
             p[j] += step;
         }
     }
 };
 
 // Fragment addressing: byte offset inside one operand stage for MFMA rows (frag_row0 + lane%32), k16-step ks.
-template <bool KMAJOR, int SWZ>
+template <bool KMAJOR, int SWZ, int ROWS>
 struct Frag {
     int off[2][2];   // [ks][kk]; kk only used for the transposing form
     __device__ __forceinline__ void init(int tile_row0, int lane)
@@ -100,7 +101,7 @@ struct Frag {
                 for (int kk = 0; kk < 2; ++kk) {
                     const int k = 16 * ks + 8 * h + 4 * kk + (i >> 2);
                     const int col = tile_row0 + 16 * blk + 4 * (i & 3);
-                    off[ks][kk] = k * 512 + (((col >> 3) ^ gswz(k)) << 4) + ((col & 7) << 1);
+                    off[ks][kk] = k * (ROWS * 2) + (((col >> 3) ^ gswz(k)) << 4) + ((col & 7) << 1);
                 }
         }
     }
@@ -128,8 +129,14 @@ struct Frag {
 #define STL_ORDER_MFMA_READS()                                  \
     do {                                                        \
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);     \
-        __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);      \
     } while (0)
 
 template <int N>
@@ -137,159 +144,226 @@ __device__ __forceinline__ void wait_vmcnt()
 {
     if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else if constexpr (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
     else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     else if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
     else static_assert(N == 0, "unsupported vmcnt");
 }
 
+#ifdef STL_GEMM_TIMELINE
+__device__ unsigned long long g_timeline[8192 * 4];
+#define STL_TSTAMP(slot)                                                                   \
+    do {                                                                                   \
+        if (threadIdx.x == 0 && v < 8192) g_timeline[v * 4 + (slot)] = __builtin_amdgcn_s_memtime(); \
+    } while (0)
+#else
+#define STL_TSTAMP(slot) do { } while (0)
+#endif
+
 }  // namespace pipe
 
 // A_T: A stored [l][i];  B_T: B stored [l][j].  Requires Kl % 32 == 0, Mi % 8 == 0, Nj % 8 == 0.
+//
+// Persistent: the grid is one workgroup per CU and every workgroup walks over its share of the
+// (plane, block) list.  When a block's MFMA loop ends, the first ring stages of the NEXT block are put in
+// flight before the epilogue starts, so the HBM/L2 latency of the refill and the store traffic of the
+// epilogue overlap instead of adding up.  The epilogue goes through a wavefront-private LDS slab (no
+// workgroup barrier): MFMA operands are passed as (B fragment, A fragment), which leaves every lane
+// with 4 consecutive output columns of one row per accumulator quad, i.e. one 8- or 16-byte LDS write.
 template <int NS, int SWZ, bool A_T, bool B_T, typename TO, bool ACC>
 __global__ __launch_bounds__(512) void gemm_pipe_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B,
                                                         TO *__restrict__ Out, int Mi, int Nj, int Kl, int tiles_m,
                                                         int tiles_n, int total)
 {
     using namespace pipe;
-    constexpr int BM = 256, BN = 256, WAVES_N = 4, WM = 128, WN = 64, FM = 4, FN = 2;
+    constexpr int BM = 256, BN = 256, WAVES_N = 4, NW = 8, WM = 128, WN = 64, FM = 4, FN = 2;
+    constexpr int OPER_BYTES = BM * BKS * 2, STAGE_BYTES = (BM + BN) * BKS * 2;
+    constexpr int DMA_PER_STAGE = (BM + BN) / 16 / NW;     // DMA instructions per wavefront and stage
+    constexpr int ES = sizeof(TO);
+    constexpr int RP = (ES == 2 ? 32 : 16) / (NS == 4 ? 2 : 1);   // rows staged per epilogue pass (LDS budget)
+    constexpr int PITCH = WN * ES + 16;                     // bytes per staged row
+    constexpr int SLAB = RP * PITCH;                        // per wavefront
+    static_assert(NS == 3 || NS == 4, "ring depth");
     extern __shared__ __align__(16) char smem[];
-
-    int bid = blockIdx.x;
-    if ((total & 7) == 0) bid = (bid & 7) * (total >> 3) + (bid >> 3);   // consecutive blocks of a plane on one XCD
-    const int per_plane = tiles_m * tiles_n;
-    const int p = bid / per_plane;
-    const int rem = bid - p * per_plane;
-    const int i0 = (rem / tiles_n) * BM, j0 = (rem % tiles_n) * BN;
-
-    A += (size_t)p * Mi * Kl;
-    B += (size_t)p * Kl * Nj;
-    Out += (size_t)p * Mi * Nj;
+    char *slab = smem + NS * STAGE_BYTES + (threadIdx.x >> 6) * SLAB;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int per_plane = tiles_m * tiles_n;
+    const int nks = Kl / BKS;
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)STL_LDS(smem);
 
-    Src<A_T, SWZ> sa;
-    Src<B_T, SWZ> sb;
-    sa.init(A, A_T ? Mi : Kl, i0, Mi, wave, lane);
-    sb.init(B, B_T ? Nj : Kl, j0, Nj, wave, lane);
-    Frag<A_T, SWZ> fa;
-    Frag<B_T, SWZ> fb;
+    Frag<A_T, SWZ, BM> fa;
+    Frag<B_T, SWZ, BN> fb;
     fa.init(wm * WM, lane);
     fb.init(wn * WN, lane);
 
-    f32x16_t acc[FM][FN];
-#pragma unroll
-    for (int a = 0; a < FM; ++a)
-#pragma unroll
-        for (int b = 0; b < FN; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    // block list: virtual block id v -> (plane, block row, block column); consecutive blocks of a plane are
+    // dealt to one XCD (hardware deals workgroup ids round-robin over the 8 XCDs)
+    auto locate = [&](int v, int &p, int &i0, int &j0) {
+        int lid = v;
+        if ((total & 7) == 0 && (gridDim.x & 7) == 0) lid = (v & 7) * (total >> 3) + (v >> 3);
+        p = lid / per_plane;
+        const int rem = lid - p * per_plane;
+        i0 = (rem / tiles_n) * BM;
+        j0 = (rem % tiles_n) * BN;
+    };
 
-    const int nks = Kl / BKS;
-    const uint32_t smem_lds = (uint32_t)(uintptr_t)STL_LDS(smem);
-    static_assert(NS == 4 || NS == 3, "ring depth");
-    // Each wavefront issues 4 DMA instructions per stage.  Stage s+NS-1 is issued in iteration s, stage s+1 must
-    // have landed at the top of iteration s (fragments are fetched one k16-step ahead, across the stage
-    // boundary), so NS-3 later stages may still be in flight there.
+    Src<A_T, SWZ, BM, NW> sa;
+    Src<B_T, SWZ, BN, NW> sb;
+    auto start_block = [&](int v) {      // point the DMA sources at block v and put its first NS-1 stages in flight
+        int p, i0, j0;
+        locate(v, p, i0, j0);
+        sa.init(A + (size_t)p * Mi * Kl, A_T ? Mi : Kl, i0, Mi, wave, lane);
+        sb.init(B + (size_t)p * Kl * Nj, B_T ? Nj : Kl, j0, Nj, wave, lane);
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s) {
-        if (s < nks) {
-            sa.issue(smem_lds + s * STAGE_BYTES, wave);
-            sb.issue(smem_lds + s * STAGE_BYTES + OPER_BYTES, wave);
-        }
-    }
-    if (nks > NS - 2) wait_vmcnt<4 * (NS - 2)>();
-    else wait_vmcnt<0>();
-    block_barrier();
-
-    bf16x8_t va[2][FM], vb[2][FN];      // fragment double buffer: [k16-step parity]
-#pragma unroll
-    for (int a = 0; a < FM; ++a) va[0][a] = fa.read(smem, a, 0);
-#pragma unroll
-    for (int b = 0; b < FN; ++b) vb[0][b] = fb.read(smem + OPER_BYTES, b, 0);
-
-    for (int s = 0; s < nks; ++s) {
-        if (s + 1 < nks) {
-            if (s + NS - 2 < nks) wait_vmcnt<4 * (NS - 3)>();
-            else wait_vmcnt<0>();
-        }
-        block_barrier();                 // stage s+1 visible to all; nobody reads stage s-1 any more
-        if (s + NS - 1 < nks) {
-            const uint32_t dst = smem_lds + ((s + NS - 1) % NS) * STAGE_BYTES;
-            sa.issue(dst, wave);
-            sb.issue(dst + OPER_BYTES, wave);
-        }
-        const char *cur = smem + (s % NS) * STAGE_BYTES;
-        const char *nxt = smem + ((s + 1) % NS) * STAGE_BYTES;
-        // k16-step 0 of stage s runs on fragments fetched during the previous step, while step 1's fragments
-        // are fetched; then step 1 runs while step 0 of stage s+1 is fetched.  The scheduling fences keep the
-        // compiler from folding the two register sets back into one (which serialises LDS latency and MFMA).
-#pragma unroll
-        for (int a = 0; a < FM; ++a) va[1][a] = fa.read(cur, a, 1);
-#pragma unroll
-        for (int b = 0; b < FN; ++b) vb[1][b] = fb.read(cur + OPER_BYTES, b, 1);
-#pragma unroll
-        for (int a = 0; a < FM; ++a)
-#pragma unroll
-            for (int b = 0; b < FN; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[0][a], vb[0][b], acc[a][b], 0, 0, 0);
-        STL_ORDER_MFMA_READS();
-        __builtin_amdgcn_sched_barrier(0);
-        // (unconditional: after the last stage this reads a stale ring slot whose values are never used;
-        //  a branch here would make the compiler drain all LDS reads before the MFMAs below)
-#pragma unroll
-        for (int a = 0; a < FM; ++a) va[0][a] = fa.read(nxt, a, 0);
-#pragma unroll
-        for (int b = 0; b < FN; ++b) vb[0][b] = fb.read(nxt + OPER_BYTES, b, 0);
-#pragma unroll
-        for (int a = 0; a < FM; ++a)
-#pragma unroll
-            for (int b = 0; b < FN; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][a], vb[1][b], acc[a][b], 0, 0, 0);
-        STL_ORDER_MFMA_READS();
-        __builtin_amdgcn_sched_barrier(0);
-    }
-
-    // Epilogue: 32 rows x WN columns per wavefront at a time through LDS, 16-byte row-contiguous stores.
-    // Accumulator layout of a 32x32 fragment: column = lane % 32, row = 8*(v/4) + 4*(lane/32) + v%4.
-    constexpr int ES = sizeof(TO);
-    constexpr int PITCH = WN * ES + 16;
-    constexpr int LPR = WN * ES / 16;
-    constexpr int RPI = 64 / LPR;
-    char *slab = smem + wave * (32 * PITCH);
-    const int frow = lane & 31, fhalf = lane >> 5;
-#pragma unroll
-    for (int a = 0; a < FM; ++a) {
-        __syncthreads();
-#pragma unroll
-        for (int b = 0; b < FN; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int rr = 8 * (v >> 2) + 4 * fhalf + (v & 3), cc = b * 32 + frow;
-                Elem<TO>::st(reinterpret_cast<TO *>(slab + rr * PITCH) + cc, acc[a][b][v]);
+        for (int s = 0; s < NS - 1; ++s) {
+            if (s < nks) {
+                sa.issue(smem_lds + s * STAGE_BYTES, wave);
+                sb.issue(smem_lds + s * STAGE_BYTES + OPER_BYTES, wave);
             }
-        __syncthreads();
-        const int gi_base = i0 + wm * WM + a * 32;
-        const int gj = j0 + wn * WN + (lane % LPR) * (16 / ES);
+        }
+    };
+
+    int v = blockIdx.x;
+    if (v < total) start_block(v);
+
+    for (; v < total; v += gridDim.x) {
+        int p, i0, j0;
+        locate(v, p, i0, j0);
+
+        f32x16_t acc[FM][FN];
 #pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it) {
-            const int rr = it * RPI + lane / LPR;
-            const int gi = gi_base + rr;
-            if (gi < Mi && gj < Nj) {
-                u32x4_t w = *reinterpret_cast<const u32x4_t *>(slab + rr * PITCH + (lane % LPR) * 16);
-                TO *o = Out + (size_t)gi * Nj + gj;
-                if (ACC) {
-                    const f32x4_t old = *reinterpret_cast<const f32x4_t *>(o);
-                    f32x4_t nw = __builtin_bit_cast(f32x4_t, w);
-                    nw += old;
-                    *reinterpret_cast<f32x4_t *>(o) = nw;
-                } else {
-                    *reinterpret_cast<u32x4_t *>(o) = w;
+        for (int a = 0; a < FM; ++a)
+#pragma unroll
+            for (int b = 0; b < FN; ++b)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+        // Stage s+NS-1 is issued in iteration s; stage s+1 must have landed at the top of iteration s (fragments
+        // are fetched one k16-step ahead, across the stage boundary).  Stores of the previous epilogue may still
+        // be in flight: "at most N operations outstanding" then over-waits but never under-waits.
+        STL_TSTAMP(0);
+        if (nks > NS - 2) wait_vmcnt<DMA_PER_STAGE * (NS - 2)>();
+        else wait_vmcnt<0>();
+        block_barrier();
+        STL_TSTAMP(1);
+
+        bf16x8_t va[2][FM], vb[2][FN];      // fragment double buffer: [k16-step parity]
+#pragma unroll
+        for (int a = 0; a < FM; ++a) va[0][a] = fa.read(smem, a, 0);
+#pragma unroll
+        for (int b = 0; b < FN; ++b) vb[0][b] = fb.read(smem + OPER_BYTES, b, 0);
+
+        for (int s = 0; s < nks; ++s) {
+            if (s + 1 < nks) {
+                if (s + NS - 2 < nks) wait_vmcnt<DMA_PER_STAGE * (NS - 3)>();
+                else wait_vmcnt<0>();
+            }
+            block_barrier();                 // stage s+1 visible to all; nobody reads stage s-1 any more
+            if (s + NS - 1 < nks) {
+                const uint32_t dst = smem_lds + ((s + NS - 1) % NS) * STAGE_BYTES;
+                sa.issue(dst, wave);
+                sb.issue(dst + OPER_BYTES, wave);
+            }
+            const char *cur = smem + (s % NS) * STAGE_BYTES;
+            const char *nxt = smem + ((s + 1) % NS) * STAGE_BYTES;
+            // k16-step 0 of stage s runs on fragments fetched during the previous step, while step 1's fragments
+            // are fetched; then step 1 runs while step 0 of stage s+1 is fetched.  The scheduling fences keep the
+            // compiler from folding the two register sets back into one (which serialises LDS latency and MFMA).
+#pragma unroll
+            for (int a = 0; a < FM; ++a) va[1][a] = fa.read(cur, a, 1);
+#pragma unroll
+            for (int b = 0; b < FN; ++b) vb[1][b] = fb.read(cur + OPER_BYTES, b, 1);
+#pragma unroll
+            for (int a = 0; a < FM; ++a)
+#pragma unroll
+                for (int b = 0; b < FN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[0][b], va[0][a], acc[a][b], 0, 0, 0);
+            STL_ORDER_MFMA_READS();
+            __builtin_amdgcn_sched_barrier(0);
+            // (unconditional: after the last stage this reads a stale ring slot whose values are never used;
+            //  a branch here would make the compiler drain all LDS reads before the MFMAs below)
+#pragma unroll
+            for (int a = 0; a < FM; ++a) va[0][a] = fa.read(nxt, a, 0);
+#pragma unroll
+            for (int b = 0; b < FN; ++b) vb[0][b] = fb.read(nxt + OPER_BYTES, b, 0);
+#pragma unroll
+            for (int a = 0; a < FM; ++a)
+#pragma unroll
+                for (int b = 0; b < FN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[1][b], va[1][a], acc[a][b], 0, 0, 0);
+            STL_ORDER_MFMA_READS();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        // every wavefront is done with the ring: refill it for the next block before storing this one
+        block_barrier();
+        STL_TSTAMP(2);
+        if (v + (int)gridDim.x < total) start_block(v + gridDim.x);
+
+        // Epilogue.  With operands passed as (B fragment, A fragment) accumulator e of fragment (a, b) is
+        //   Out[row = 32a + lane%32][column = 32b + 8*(e/4) + 4*(lane/32) + e%4].
+        TO *outp = Out + (size_t)p * Mi * Nj;
+        const int frow = lane & 31, fhalf = lane >> 5;
+        constexpr int LPR = WN * ES / 16;                   // lanes per row in the store phase
+        constexpr int RPI = 64 / LPR;                       // rows per store instruction
+#pragma unroll
+        for (int a = 0; a < FM; ++a) {
+#pragma unroll
+            for (int pass = 0; pass < 32 / RP; ++pass) {
+                if (RP == 32 || (frow / RP) == pass) {
+                    char *rowp = slab + (frow % RP) * PITCH;
+#pragma unroll
+                    for (int b = 0; b < FN; ++b)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const int cc = b * 32 + 8 * g + 4 * fhalf;
+                            if (ES == 2) {
+                                const u32x2_t w = {pack_bf16x2(acc[a][b][4 * g], acc[a][b][4 * g + 1]),
+                                                   pack_bf16x2(acc[a][b][4 * g + 2], acc[a][b][4 * g + 3])};
+                                *reinterpret_cast<u32x2_t *>(rowp + cc * 2) = w;
+                            } else {
+                                const f32x4_t w = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
+                                                   acc[a][b][4 * g + 3]};
+                                *reinterpret_cast<f32x4_t *>(rowp + cc * 4) = w;
+                            }
+                        }
                 }
+                // same wavefront wrote the slab; LDS operations of a wavefront complete in order
+                asm volatile("" ::: "memory");
+                const int gi_base = i0 + wm * WM + a * 32 + pass * RP;
+                const int gj = j0 + wn * WN + (lane % LPR) * (16 / ES);
+#pragma unroll
+                for (int it = 0; it < RP / RPI; ++it) {
+                    const int rr = it * RPI + lane / LPR;
+                    const int gi = gi_base + rr;
+                    const u32x4_t w = *reinterpret_cast<const u32x4_t *>(slab + rr * PITCH + (lane % LPR) * 16);
+                    if (gi < Mi && gj < Nj) {
+                        TO *o = outp + (size_t)gi * Nj + gj;
+                        if (ACC) {
+                            const f32x4_t old = *reinterpret_cast<const f32x4_t *>(o);
+                            f32x4_t nw = __builtin_bit_cast(f32x4_t, w);
+                            nw += old;
+                            *reinterpret_cast<f32x4_t *>(o) = nw;
+                        } else {
+                            *reinterpret_cast<u32x4_t *>(o) = w;
+                        }
+                    }
+                }
+                asm volatile("" ::: "memory");
             }
         }
+        STL_TSTAMP(3);
     }
 }
+
+#ifdef STL_GEMM_TIMELINE
+extern "C" int stl_debug_timeline(unsigned long long *host_out, int n)
+{
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(pipe::g_timeline), sizeof(unsigned long long) * n);
+}
+#endif
 
 bool plane_gemm_pipe_eligible(const GemmDesc &g)
 {
@@ -300,11 +374,25 @@ bool plane_gemm_pipe_eligible(const GemmDesc &g)
     return g.Mi > 128 && g.Nj > 128;
 }
 
-template <int NS, int SWZ, bool A_T, bool B_T, typename TO, bool ACC>
+static int cu_count()
+{
+    static const int n = []() {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+        return cus;
+    }();
+    return n;
+}
+
+template <bool A_T, bool B_T, typename TO, bool ACC>
 static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
+    constexpr int NS = 4, SWZ = 1;
     auto kern = gemm_pipe_kernel<NS, SWZ, A_T, B_T, TO, ACC>;
-    constexpr int smem = NS * pipe::STAGE_BYTES;
+    constexpr int ES = sizeof(TO);
+    constexpr int smem = NS * 512 * pipe::BKS * 2 + 8 * ((ES == 2 ? 32 : 16) / (NS == 4 ? 2 : 1)) * (64 * ES + 16);
+    static_assert(smem <= 160 * 1024, "LDS budget");
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -315,28 +403,23 @@ static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *
     const int tiles_m = (g.Mi + 255) / 256, tiles_n = (g.Nj + 255) / 256;
     const long total = (long)tiles_m * tiles_n * g.batch;
     if (total > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(512), smem, s, (const bf16_t *)A, (const bf16_t *)B, (TO *)Out,
-                       g.Mi, g.Nj, g.Kl, tiles_m, tiles_n, (int)total);
+    // one block per workgroup by default; STL_GEMM_PERSIST=1 launches one workgroup per CU that walks the block list
+    static const bool persist = []() { const char *e = getenv("STL_GEMM_PERSIST"); return e && atoi(e) != 0; }();
+    const int cus = cu_count();
+    const unsigned grid = (unsigned)((persist && total > cus) ? cus : total);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), smem, s, (const bf16_t *)A, (const bf16_t *)B, (TO *)Out, g.Mi, g.Nj,
+                       g.Kl, tiles_m, tiles_n, (int)total);
     return hipGetLastError();
-}
-
-template <int NS, int SWZ>
-static hipError_t launch_pipe_form(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
-{
-    if (g.out_f32) {
-        return g.accumulate ? launch_pipe_cfg<NS, SWZ, true, true, float, true>(g, A, B, Out, s)
-                            : launch_pipe_cfg<NS, SWZ, true, true, float, false>(g, A, B, Out, s);
-    }
-    if (g.b_kmajor) return launch_pipe_cfg<NS, SWZ, false, true, bf16_t, false>(g, A, B, Out, s);
-    return launch_pipe_cfg<NS, SWZ, false, false, bf16_t, false>(g, A, B, Out, s);
 }
 
 hipError_t launch_plane_gemm_pipe(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
-    static const int swz = []() { const char *e = getenv("STL_GEMM_SWZ"); return e ? atoi(e) : 1; }();
-    static const int ns = []() { const char *e = getenv("STL_GEMM_NS"); return e ? atoi(e) : 4; }();
-    if (ns == 3) return swz == 2 ? launch_pipe_form<3, 2>(g, A, B, Out, s) : launch_pipe_form<3, 1>(g, A, B, Out, s);
-    return swz == 2 ? launch_pipe_form<4, 2>(g, A, B, Out, s) : launch_pipe_form<4, 1>(g, A, B, Out, s);
+    if (g.out_f32) {
+        return g.accumulate ? launch_pipe_cfg<true, true, float, true>(g, A, B, Out, s)
+                            : launch_pipe_cfg<true, true, float, false>(g, A, B, Out, s);
+    }
+    if (g.b_kmajor) return launch_pipe_cfg<false, true, bf16_t, false>(g, A, B, Out, s);
+    return launch_pipe_cfg<false, false, bf16_t, false>(g, A, B, Out, s);
 }
 
 }  // namespace stl

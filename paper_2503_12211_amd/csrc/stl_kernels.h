@@ -38,4 +38,10 @@ hipError_t launch_plane_gemm_mfma(const GemmDesc &g, const void *A, const void *
 bool plane_gemm_pipe_eligible(const GemmDesc &g);
 hipError_t launch_plane_gemm_pipe(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s);
 
+// Forward on one output block with all planes resident (decode in the epilogue).  encode_in_kernel: Xin is X
+// (single-launch fused form); otherwise Xin is Xhat.  Ysave may be NULL.  bf16 storage only.
+bool block_forward_eligible(int dtype, int M, int K, int N, int r);
+hipError_t launch_block_forward(bool encode_in_kernel, const void *Xin, const void *What, const void *E, const void *Dm,
+                                void *C, void *Ysave, int M, int K, int N, int r, bool gelu, hipStream_t s);
+
 }  // namespace stl

@@ -76,3 +76,19 @@ def test_workspace_grows_with_problem():
     b = stl.stl_workspace_bytes(stl.Problem(512, 256, 256, 32), stl.STL_OP_BACKWARD)
     assert 0 < a < b
     assert stl.stl_workspace_bytes(stl.Problem(256, 256, 256, 32), stl.STL_OP_ENCODE_WEIGHT) == 0
+
+
+def test_block_resident_variants_reject_unsupported_shapes():
+    for kw in (dict(r=49), dict(k=96), dict(n=40), dict(dtype=stl.STL_F32)):
+        base = dict(m=256, k=256, n=256, r=32, dtype=stl.STL_BF16)
+        base.update(kw)
+        prob = stl.Problem(**base)
+        for flag in (stl.STL_FLAG_EPILOGUE, stl.STL_FLAG_FUSED):
+            with pytest.raises(stl.StlError) as e:
+                stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 1 << 40, flag, stream=0)
+            assert e.value.status == 2
+    prob = stl.Problem(256, 256, 256, 32)
+    with pytest.raises(stl.StlError) as e:      # the fused variant never materialises Xhat
+        stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, 1 << 40, stl.STL_FLAG_FUSED, stream=0)
+    assert e.value.status == 2
+    assert stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD, stl.STL_FLAG_FUSED) == 0

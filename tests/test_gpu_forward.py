@@ -141,3 +141,52 @@ def test_forward_is_deterministic(gu):
     a = gu.forward(p, "bf16")
     b = gu.forward(p, "bf16")
     assert np.array_equal(a, b)
+
+
+VARIANT_SHAPES = [  # (m, k, n, r): k % 64 == 0, n % 32 == 0; blocks hang over the edge in m and n
+    (128, 64, 32, 1), (132, 128, 96, 7), (1056, 576, 800, 24), (516, 1024, 544, 32), (2048, 512, 1024, 8),
+]
+
+
+@pytest.mark.parametrize("variant", ["epilogue", "fused"])
+@pytest.mark.parametrize("shape", VARIANT_SHAPES)
+def test_forward_block_resident_variants(gu, variant, shape):
+    """Decode-in-epilogue and single-launch fused forward against Eq. (2); Yhat written on request."""
+    import paper_2503_12211_amd as stl
+    m, k, n, r = shape
+    flag = {"epilogue": stl.STL_FLAG_EPILOGUE, "fused": stl.STL_FLAG_FUSED}[variant]
+    p = stl_synth.stl_problem(m, k, n, r, seed=301 + m + r, dtype="bf16")
+    Cref, Yref = planes.forward(p["X"], p["What"], p["E_X"], p["D"], return_yhat=True)
+    C, Y = gu.forward(p, "bf16", flags=flag, save_yhat=True)
+    assert gu.rel(C, Cref) <= gu.TOL["bf16"]
+    assert gu.rel(Y, Yref) <= gu.TOL["bf16"]
+    C2 = gu.forward(p, "bf16", flags=flag | stl.STL_FLAG_GELU)
+    assert gu.rel(C2, planes.gelu(Cref)) <= gu.TOL["bf16"]
+    M, N = m // 4, n // 4
+    blk = oracle.forward_block(p["X"], p["What"], p["E_X"], p["D"], max(M - 3, 0), M, max(N - 5, 0), N)
+    assert gu.rel(C[4 * max(M - 3, 0):, 4 * max(N - 5, 0):], blk) <= 2 * gu.TOL["bf16"]
+
+
+def test_forward_variants_agree_at_config2_shape(gu):
+    """bf16, m=k=n=4096, r=32: all three forward variants against the plane oracle."""
+    import paper_2503_12211_amd as stl
+    cfg, p = stl_synth.config_problem("C2")
+    Cref = planes.forward(p["X"], p["What"], p["E_X"], p["D"])
+    for flag in (stl.STL_FLAG_UNFUSED, stl.STL_FLAG_EPILOGUE, stl.STL_FLAG_FUSED):
+        assert gu.rel(gu.forward(p, "bf16", flags=flag), Cref) <= gu.TOL["bf16"], flag
+
+
+@pytest.mark.parametrize("full", [False, True])
+def test_mlp_shaped_pair(gu, full):
+    """Up-projection, GELU (in the first layer's decode), down-projection, r=24; the hidden activation is rounded
+    to bf16 between the layers on the GPU, the oracle stays in fp64 throughout."""
+    import paper_2503_12211_amd as stl
+    m, d, h, r = (16384, 1024, 4096, 24) if full else (512, 256, 1024, 24)
+    p1 = stl_synth.stl_problem(m, d, h, r, seed=stl_synth.SEEDS["C4_up"], dtype="bf16")
+    p2 = stl_synth.stl_problem(m, h, d, r, seed=stl_synth.SEEDS["C4_down"], dtype="bf16")
+    H = gu.forward(p1, "bf16", flags=stl.STL_FLAG_GELU)
+    q2 = dict(p2)
+    q2["X"] = H.astype(np.float32)
+    out = gu.forward(q2, "bf16")
+    ref = planes.mlp_pair(p1["X"], p1["What"], p1["E_X"], p1["D"], p2["What"], p2["E_X"], p2["D"])
+    assert gu.rel(out, ref) <= gu.TOL["bf16"]

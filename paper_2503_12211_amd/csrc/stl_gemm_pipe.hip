@@ -15,6 +15,7 @@
 #include "stl_device.h"
 
 #include <cstdlib>
+#include <type_traits>
 
 namespace stl {
 
@@ -124,20 +125,52 @@ struct Frag {
     }
 };
 
-// Instruction order inside one k16-step: the first MFMA (whose operands were fetched a whole step ago), then all
-// LDS reads of the following step, then the remaining MFMAs -- so that no LDS latency sits in front of an MFMA.
-#define STL_ORDER_MFMA_READS()                                  \
-    do {                                                        \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);      \
-    } while (0)
+// Instruction order inside one k16-step: MFMAs whose operands were fetched a whole step ago are interleaved with
+// the LDS reads of the following step (a few reads after each of the first MFMAs), so that no LDS latency sits
+// in front of an MFMA and the reads of the wavefronts do not arrive at the LDS in one burst.
+template <int NMFMA>
+__device__ __forceinline__ void order_mfma_reads()
+{
+    if constexpr (NMFMA == 8) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    } else {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    }
+}
+
+// compile-time loop: the body sees its index as a constant, so register arrays are never indexed dynamically
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
@@ -147,6 +180,7 @@ __device__ __forceinline__ void wait_vmcnt()
     else if constexpr (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
     else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     else if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    else if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     else static_assert(N == 0, "unsupported vmcnt");
 }
 
@@ -170,17 +204,18 @@ __device__ unsigned long long g_timeline[8192 * 4];
 // epilogue overlap instead of adding up.  The epilogue goes through a wavefront-private LDS slab (no
 // workgroup barrier): MFMA operands are passed as (B fragment, A fragment), which leaves every lane
 // with 4 consecutive output columns of one row per accumulator quad, i.e. one 8- or 16-byte LDS write.
-template <int NS, int SWZ, bool A_T, bool B_T, typename TO, bool ACC>
-__global__ __launch_bounds__(512) void gemm_pipe_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B,
+template <int WAVES_M, int WAVES_N, int NS, int SWZ, bool A_T, bool B_T, typename TO, bool ACC>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B,
                                                         TO *__restrict__ Out, int Mi, int Nj, int Kl, int tiles_m,
                                                         int tiles_n, int total)
 {
     using namespace pipe;
-    constexpr int BM = 256, BN = 256, WAVES_N = 4, NW = 8, WM = 128, WN = 64, FM = 4, FN = 2;
+    constexpr int BM = 256, BN = 256, NW = WAVES_M * WAVES_N, WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int FM = WM / 32, FN = WN / 32;
     constexpr int OPER_BYTES = BM * BKS * 2, STAGE_BYTES = (BM + BN) * BKS * 2;
     constexpr int DMA_PER_STAGE = (BM + BN) / 16 / NW;     // DMA instructions per wavefront and stage
     constexpr int ES = sizeof(TO);
-    constexpr int RP = (ES == 2 ? 32 : 16) / (NS == 4 ? 2 : 1);   // rows staged per epilogue pass (LDS budget)
+    constexpr int RP = (ES == 2 ? 32 : 16) / (NS == 4 ? 2 : 1) / (WN / 64);   // rows staged per epilogue pass (LDS budget)
     constexpr int PITCH = WN * ES + 16;                     // bytes per staged row
     constexpr int SLAB = RP * PITCH;                        // per wavefront
     static_assert(NS == 3 || NS == 4, "ring depth");
@@ -280,7 +315,7 @@ __global__ __launch_bounds__(512) void gemm_pipe_kernel(const bf16_t *__restrict
 #pragma unroll
                 for (int b = 0; b < FN; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[0][b], va[0][a], acc[a][b], 0, 0, 0);
-            STL_ORDER_MFMA_READS();
+            order_mfma_reads<FM * FN>();
             __builtin_amdgcn_sched_barrier(0);
             // (unconditional: after the last stage this reads a stale ring slot whose values are never used;
             //  a branch here would make the compiler drain all LDS reads before the MFMAs below)
@@ -293,7 +328,7 @@ __global__ __launch_bounds__(512) void gemm_pipe_kernel(const bf16_t *__restrict
 #pragma unroll
                 for (int b = 0; b < FN; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[1][b], va[1][a], acc[a][b], 0, 0, 0);
-            STL_ORDER_MFMA_READS();
+            order_mfma_reads<FM * FN>();
             __builtin_amdgcn_sched_barrier(0);
         }
 
@@ -308,10 +343,10 @@ __global__ __launch_bounds__(512) void gemm_pipe_kernel(const bf16_t *__restrict
         const int frow = lane & 31, fhalf = lane >> 5;
         constexpr int LPR = WN * ES / 16;                   // lanes per row in the store phase
         constexpr int RPI = 64 / LPR;                       // rows per store instruction
-#pragma unroll
-        for (int a = 0; a < FM; ++a) {
-#pragma unroll
-            for (int pass = 0; pass < 32 / RP; ++pass) {
+        static_for<0, FM>([&](auto a_c) {
+            constexpr int a = decltype(a_c)::value;
+            static_for<0, 32 / RP>([&](auto pass_c) {
+                constexpr int pass = decltype(pass_c)::value;
                 if (RP == 32 || (frow / RP) == pass) {
                     char *rowp = slab + (frow % RP) * PITCH;
 #pragma unroll
@@ -352,8 +387,8 @@ __global__ __launch_bounds__(512) void gemm_pipe_kernel(const bf16_t *__restrict
                     }
                 }
                 asm volatile("" ::: "memory");
-            }
-        }
+            });
+        });
         STL_TSTAMP(3);
     }
 }
@@ -385,13 +420,14 @@ static int cu_count()
     return n;
 }
 
-template <bool A_T, bool B_T, typename TO, bool ACC>
+template <int WAVES_M, int WAVES_N, bool A_T, bool B_T, typename TO, bool ACC>
 static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
-    constexpr int NS = 4, SWZ = 1;
-    auto kern = gemm_pipe_kernel<NS, SWZ, A_T, B_T, TO, ACC>;
+    constexpr int NS = 4, SWZ = 1, NW = WAVES_M * WAVES_N, WN = 256 / WAVES_N;
+    auto kern = gemm_pipe_kernel<WAVES_M, WAVES_N, NS, SWZ, A_T, B_T, TO, ACC>;
     constexpr int ES = sizeof(TO);
-    constexpr int smem = NS * 512 * pipe::BKS * 2 + 8 * ((ES == 2 ? 32 : 16) / (NS == 4 ? 2 : 1)) * (64 * ES + 16);
+    constexpr int RP = (ES == 2 ? 32 : 16) / (NS == 4 ? 2 : 1) / (WN / 64);
+    constexpr int smem = NS * 512 * pipe::BKS * 2 + NW * RP * (WN * ES + 16);
     static_assert(smem <= 160 * 1024, "LDS budget");
     static bool attr_set = false;
     if (!attr_set) {
@@ -407,19 +443,29 @@ static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *
     static const bool persist = []() { const char *e = getenv("STL_GEMM_PERSIST"); return e && atoi(e) != 0; }();
     const int cus = cu_count();
     const unsigned grid = (unsigned)((persist && total > cus) ? cus : total);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(512), smem, s, (const bf16_t *)A, (const bf16_t *)B, (TO *)Out, g.Mi, g.Nj,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), smem, s, (const bf16_t *)A, (const bf16_t *)B, (TO *)Out, g.Mi, g.Nj,
                        g.Kl, tiles_m, tiles_n, (int)total);
     return hipGetLastError();
 }
 
-hipError_t launch_plane_gemm_pipe(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
+template <int WAVES_M, int WAVES_N>
+static hipError_t launch_pipe_form(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
     if (g.out_f32) {
-        return g.accumulate ? launch_pipe_cfg<true, true, float, true>(g, A, B, Out, s)
-                            : launch_pipe_cfg<true, true, float, false>(g, A, B, Out, s);
+        return g.accumulate ? launch_pipe_cfg<WAVES_M, WAVES_N, true, true, float, true>(g, A, B, Out, s)
+                            : launch_pipe_cfg<WAVES_M, WAVES_N, true, true, float, false>(g, A, B, Out, s);
     }
-    if (g.b_kmajor) return launch_pipe_cfg<false, true, bf16_t, false>(g, A, B, Out, s);
-    return launch_pipe_cfg<false, false, bf16_t, false>(g, A, B, Out, s);
+    if (g.b_kmajor) return launch_pipe_cfg<WAVES_M, WAVES_N, false, true, bf16_t, false>(g, A, B, Out, s);
+    return launch_pipe_cfg<WAVES_M, WAVES_N, false, false, bf16_t, false>(g, A, B, Out, s);
+}
+
+hipError_t launch_plane_gemm_pipe(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
+{
+    // eight wavefronts of 128 x 64, or four of 128 x 128 (a third less LDS fragment traffic per MFMA, but a single
+    // wavefront per SIMD has to keep its own MFMA pipe full)
+    static const int waves = []() { const char *e = getenv("STL_GEMM_WAVES"); return e ? atoi(e) : 8; }();
+    if (waves == 4) return launch_pipe_form<2, 2>(g, A, B, Out, s);
+    return launch_pipe_form<2, 4>(g, A, B, Out, s);
 }
 
 }  // namespace stl

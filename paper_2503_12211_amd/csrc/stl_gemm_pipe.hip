@@ -207,7 +207,7 @@ __device__ unsigned long long g_timeline[8192 * 4];
 template <int WAVES_M, int WAVES_N, int NS, int SWZ, bool A_T, bool B_T, typename TO, bool ACC>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B,
                                                         TO *__restrict__ Out, int Mi, int Nj, int Kl, int tiles_m,
-                                                        int tiles_n, int total)
+                                                        int tiles_n, int total, int dbg)
 {
     using namespace pipe;
     constexpr int BM = 256, BN = 256, NW = WAVES_M * WAVES_N, WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -343,6 +343,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
         const int frow = lane & 31, fhalf = lane >> 5;
         constexpr int LPR = WN * ES / 16;                   // lanes per row in the store phase
         constexpr int RPI = 64 / LPR;                       // rows per store instruction
+        if (!(dbg & 2))
         static_for<0, FM>([&](auto a_c) {
             constexpr int a = decltype(a_c)::value;
             static_for<0, 32 / RP>([&](auto pass_c) {
@@ -374,7 +375,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
                     const int rr = it * RPI + lane / LPR;
                     const int gi = gi_base + rr;
                     const u32x4_t w = *reinterpret_cast<const u32x4_t *>(slab + rr * PITCH + (lane % LPR) * 16);
-                    if (gi < Mi && gj < Nj) {
+                    if (gi < Mi && gj < Nj && !(dbg & 1)) {
                         TO *o = outp + (size_t)gi * Nj + gj;
                         if (ACC) {
                             const f32x4_t old = *reinterpret_cast<const f32x4_t *>(o);
@@ -439,12 +440,13 @@ static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *
     const int tiles_m = (g.Mi + 255) / 256, tiles_n = (g.Nj + 255) / 256;
     const long total = (long)tiles_m * tiles_n * g.batch;
     if (total > 0x7fffffffL) return hipErrorInvalidValue;
-    // one block per workgroup by default; STL_GEMM_PERSIST=1 launches one workgroup per CU that walks the block list
-    static const bool persist = []() { const char *e = getenv("STL_GEMM_PERSIST"); return e && atoi(e) != 0; }();
+    // one workgroup per CU that walks the block list (STL_GEMM_PERSIST=0: one block per workgroup)
+    static const bool persist = []() { const char *e = getenv("STL_GEMM_PERSIST"); return !e || atoi(e) != 0; }();
     const int cus = cu_count();
     const unsigned grid = (unsigned)((persist && total > cus) ? cus : total);
+    static const int dbg = []() { const char *e = getenv("STL_GEMM_DBG"); return e ? atoi(e) : 0; }();
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), smem, s, (const bf16_t *)A, (const bf16_t *)B, (TO *)Out, g.Mi, g.Nj,
-                       g.Kl, tiles_m, tiles_n, (int)total);
+                       g.Kl, tiles_m, tiles_n, (int)total, dbg);
     return hipGetLastError();
 }
 

@@ -26,7 +26,10 @@ constexpr int BKS = 32;                 // contraction elements per stage
 typedef short v4i16_t __attribute__((ext_vector_type(4)));
 #define STL_LDS(p) ((__attribute__((address_space(3))) char *)(p))
 
-// swizzles (16-byte chunk index XOR), chosen so that one access phase touches every bank once
+// Swizzles (16-byte chunk index XOR), chosen so that one access phase touches every bank once.  Measured with the
+// SQ_LDS_BANK_CONFLICT counter: ds_read_b128 is served in four phases of 16 lanes, {0-3, 12-15, 20-23, 24-27},
+// {4-11, 16-19, 28-31} and the same +32; for 64-byte rows read by lane = row, XOR with (row >> 2) & 3 is
+// conflict-free (6 LDS cycles per instruction), (row >> 1) & 3 costs 4 extra cycles, no swizzle 12.
 template <int SHIFT>
 __device__ __forceinline__ int fswz(int row) { return (row >> SHIFT) & 3; }     // [row][l] operand, 4 chunks per row
 __device__ __forceinline__ int gswz(int k) { return (k & 3) << 2; }              // [l][row] operand, 32 chunks per row
@@ -69,6 +72,12 @@ struct Src {
             }
         }
         step = KMAJOR ? (long)BKS * ld : BKS;
+    }
+    // instruction j of this wavefront's share (the main loop spreads them between MFMAs)
+    __device__ __forceinline__ void issue_one(uint32_t oper_stage, int wave, int j)
+    {
+        dma16(p[j], oper_stage + (NI * wave + j) * 1024);
+        p[j] += step;
     }
     __device__ __forceinline__ void issue(uint32_t oper_stage, int wave)   // LDS byte address of the operand stage
     {
@@ -291,45 +300,58 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
         for (int b = 0; b < FN; ++b) vb[0][b] = fb.read(smem + OPER_BYTES, b, 0);
 
         for (int s = 0; s < nks; ++s) {
-            if (s + 1 < nks) {
+            if (s + 1 < nks && !(dbg & 8)) {
                 if (s + NS - 2 < nks) wait_vmcnt<DMA_PER_STAGE * (NS - 3)>();
                 else wait_vmcnt<0>();
             }
-            block_barrier();                 // stage s+1 visible to all; nobody reads stage s-1 any more
-            if (s + NS - 1 < nks) {
-                const uint32_t dst = smem_lds + ((s + NS - 1) % NS) * STAGE_BYTES;
-                sa.issue(dst, wave);
-                sb.issue(dst + OPER_BYTES, wave);
-            }
+            if (!(dbg & 4)) block_barrier();   // stage s+1 visible to all; nobody reads stage s-1 any more
+            const bool refill = s + NS - 1 < nks && !(dbg & 16);
+            const uint32_t dst = smem_lds + ((s + NS - 1) % NS) * STAGE_BYTES;
             const char *cur = smem + (s % NS) * STAGE_BYTES;
             const char *nxt = smem + ((s + 1) % NS) * STAGE_BYTES;
-            // k16-step 0 of stage s runs on fragments fetched during the previous step, while step 1's fragments
-            // are fetched; then step 1 runs while step 0 of stage s+1 is fetched.  The scheduling fences keep the
-            // compiler from folding the two register sets back into one (which serialises LDS latency and MFMA).
-#pragma unroll
-            for (int a = 0; a < FM; ++a) va[1][a] = fa.read(cur, a, 1);
-#pragma unroll
-            for (int b = 0; b < FN; ++b) vb[1][b] = fb.read(cur + OPER_BYTES, b, 1);
-#pragma unroll
-            for (int a = 0; a < FM; ++a)
-#pragma unroll
-                for (int b = 0; b < FN; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[0][b], va[0][a], acc[a][b], 0, 0, 0);
-            order_mfma_reads<FM * FN>();
-            __builtin_amdgcn_sched_barrier(0);
-            // (unconditional: after the last stage this reads a stale ring slot whose values are never used;
-            //  a branch here would make the compiler drain all LDS reads before the MFMAs below)
-#pragma unroll
-            for (int a = 0; a < FM; ++a) va[0][a] = fa.read(nxt, a, 0);
-#pragma unroll
-            for (int b = 0; b < FN; ++b) vb[0][b] = fb.read(nxt + OPER_BYTES, b, 0);
-#pragma unroll
-            for (int a = 0; a < FM; ++a)
-#pragma unroll
-                for (int b = 0; b < FN; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[1][b], va[1][a], acc[a][b], 0, 0, 0);
-            order_mfma_reads<FM * FN>();
-            __builtin_amdgcn_sched_barrier(0);
+            // One k16-step: MFMAs run on fragments fetched during the previous step while the fragments of the
+            // following step are fetched (A fragments after the first MFMA, B fragments after the second) and
+            // this wavefront's share of the refill DMA is issued one instruction at a time further down.  Issuing
+            // the DMA in one burst right after the barrier backs up the vector-memory queue of all eight
+            // wavefronts at once and holds their MFMAs behind it; the fences pin the interleaving.
+            auto step = [&](auto par_c, const char *src, int ks, bool a_side) {
+                constexpr int par = decltype(par_c)::value;
+                static_for<0, FM * FN>([&](auto i_c) {
+                    constexpr int i = decltype(i_c)::value, a = i / FN, b = i % FN;
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[par][b], va[par][a], acc[a][b], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    // one fragment fetch per MFMA slot, in the order the next step consumes them: B0, A0, B1, A1, ...
+                    // (eight wavefronts fetching all their fragments at once fill the LDS queue, and a wavefront
+                    //  stuck issuing an LDS read cannot issue the independent MFMAs behind it)
+                    if constexpr (i < FM + FN) if (!(dbg & 32)) {
+                        constexpr int pairs = FM < FN ? FM : FN;
+                        if constexpr (i < 2 * pairs) {
+                            if constexpr ((i % 2) == 0) vb[par ^ 1][i / 2] = fb.read(src + OPER_BYTES, i / 2, ks);
+                            else va[par ^ 1][i / 2] = fa.read(src, i / 2, ks);
+                        } else if constexpr (FM > FN) {
+                            va[par ^ 1][i - pairs] = fa.read(src, i - pairs, ks);
+                        } else {
+                            vb[par ^ 1][i - pairs] = fb.read(src + OPER_BYTES, i - pairs, ks);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if constexpr (i >= 2 && (i % 2) == 0) {
+                        constexpr int j = (i - 2) / 2;       // DMA slot inside this step
+                        if (refill) {
+                            if (a_side) {
+                                if (j < decltype(sa)::NI) sa.issue_one(dst, wave, j);
+                            } else {
+                                if (j < decltype(sb)::NI) sb.issue_one(dst + OPER_BYTES, wave, j);
+                            }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                });
+            };
+            // step 0 of stage s (fetch step 1 of stage s; refill the A operand), then step 1 (fetch step 0 of stage
+            // s+1 -- after the last stage that reads a stale ring slot whose values are never used; refill B)
+            step(std::integral_constant<int, 0>{}, cur, 1, true);
+            step(std::integral_constant<int, 1>{}, nxt, 0, false);
         }
 
         // every wavefront is done with the ring: refill it for the next block before storing this one
@@ -424,7 +446,10 @@ static int cu_count()
 template <int WAVES_M, int WAVES_N, bool A_T, bool B_T, typename TO, bool ACC>
 static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
-    constexpr int NS = 4, SWZ = 1, NW = WAVES_M * WAVES_N, WN = 256 / WAVES_N;
+#ifndef STL_GEMM_NS
+#define STL_GEMM_NS 4
+#endif
+    constexpr int NS = STL_GEMM_NS, SWZ = 2, NW = WAVES_M * WAVES_N, WN = 256 / WAVES_N;
     auto kern = gemm_pipe_kernel<WAVES_M, WAVES_N, NS, SWZ, A_T, B_T, TO, ACC>;
     constexpr int ES = sizeof(TO);
     constexpr int RP = (ES == 2 ? 32 : 16) / (NS == 4 ? 2 : 1) / (WN / 64);

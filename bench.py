@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--workload", default="C5", help="C5 (default), C2, or m,k,n,r")
     ap.add_argument("--sweep", action="store_true", help="also time the forward r sweep (m=8192,k=n=4096)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--profile-only", default="", help="run only this leg (forward|backward|stages) a few times")
+    ap.add_argument("--profile-only", default="", help="run only this leg (forward|backward|step|stages|copy) a few times")
     return ap.parse_args()
 
 
@@ -45,8 +45,8 @@ def flops_model(m, k, n, r):
     M, K, N = m // 4, k // 4, n // 4
     gemm = 2.0 * r * M * K * N
     fwd = gemm + 2.0 * m * k * r + 2.0 * m * n * r
-    # backward: encode X, encode dC, two plane products, decode dX, two basis-gradient reductions
-    bwd = 2 * gemm + 2.0 * m * k * r + 2.0 * m * n * r + 2.0 * m * k * r + 2.0 * 16 * r * (M * N + M * K)
+    # backward (Xhat and Yhat saved by the forward): encode dC, two plane products, decode dX, two basis-gradient sums
+    bwd = 2 * gemm + 2.0 * m * n * r + 2.0 * m * k * r + 2.0 * 16 * r * (M * N + M * K)
     return gemm, fwd, bwd
 
 
@@ -79,6 +79,21 @@ class Timer:
         e1.record()
         t.cuda.synchronize()
         return e0.elapsed_time(e1) / steps
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc runs (FETCH_SIZE and WRITE_SIZE,
+    scaled by what the same counters read for a plain copy), or None for workloads that were not profiled."""
+    path = os.path.join(ROOT, "profiles", "plane_gemm_C5_traffic.json")
+    try:
+        with open(path) as f:
+            t = json.load(f)
+    except OSError:
+        return None
+    if t.get("workload") != workload:
+        return None
+    return {"hbm_bytes": round(t["fetch_bytes"] + t["write_bytes"]), "fetch_bytes": round(t["fetch_bytes"]),
+            "write_bytes": round(t["write_bytes"]), "source": t["source"]}
 
 
 def main():
@@ -140,7 +155,10 @@ def main():
         bwd()
 
     if args.profile_only:
+        cal_src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda")
+        cal_dst = torch.empty_like(cal_src)
         legs = {"forward": fwd_nosave, "backward": bwd, "step": step,
+                "copy": lambda: cal_dst.copy_(cal_src),      # 256 MiB read + 256 MiB written: counter calibration
                 "stages": lambda: (stl.stl_encode_activation(prob, X, E_X, Xhat),
                                    stl.stl_plane_matmul(prob, Xhat, What, Yhat),
                                    stl.stl_decode(prob, Yhat, D, C))}
@@ -212,10 +230,24 @@ def main():
             "decode": {"ms": round(ms_dec, 5), "GBps": round(dec_bytes / ms_dec / 1e6, 1),
                        "frac_hbm_peak": round(dec_bytes / ms_dec / 1e6 / PEAK_HBM_GBS, 4)},
         },
-        "roofline": {"kernel": "gemm_mfma_kernel (forward plane products, one launch)", "bound": "mfma",
+        "roofline": {"kernel": "gemm_pipe_kernel (forward plane products Yhat[p] = Xhat[p] What[p], one launch, "
+                               "2*r*M*K*N flops)", "bound": "mfma",
                      "achieved": round(tf(gemm_flop, ms_gemm), 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tf(gemm_flop, ms_gemm) / PEAK_BF16_TFLOPS, 4), "traffic": None},
+                     "frac": round(tf(gemm_flop, ms_gemm) / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(wname)},
     }
+
+    # the other forward variants at the same workload (STL_FLAG_AUTO runs the three-launch path)
+    variants = {}
+    for name, flag in (("unfused", stl.STL_FLAG_UNFUSED), ("epilogue", stl.STL_FLAG_EPILOGUE), ("fused", stl.STL_FLAG_FUSED)):
+        try:
+            nv = stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD, flag)
+            assert nv <= nf
+            variants[name] = round(T.wall(lambda: stl.stl_forward(prob, X, What, E_X, D, C, None, None, ws_f, nf, flag),
+                                          max(S // 4, 2), 1), 5)
+        except stl.StlError:
+            variants[name] = None
+    out["forward_variants_ms"] = variants
+    log(f"  forward variants (ms): {variants}")
 
     if args.sweep:
         sweep = {}
@@ -238,23 +270,23 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        sm = 2048                                  # bounded sample: the m=k=n=2048 sub-problem, same r and distributions
-        q = stl_synth.stl_problem(sm, sm, sm, r, seed + 1, "bf16", with_dC=True)
+        sm = 2048                                  # bounded sample: the m=4096, k=n=2048 sub-problem, same r and distributions
+        q = stl_synth.stl_problem(2 * sm, sm, sm, r, seed + 1, "bf16", with_dC=True)
         t0 = time.perf_counter()
         oracle.forward(q["X"], q["What"], q["E_X"], q["D"])
         oracle.backward(q["X"], q["What"], q["E_X"], q["D"], q["dC"])
         dt = time.perf_counter() - t0
-        scale = (m / sm) * (k / sm) * (n / sm)
+        scale = (m / (2 * sm)) * (k / sm) * (n / sm)
         full_ms = dt * scale * 1e3
         out["cpu_baseline"] = {
             "value": round(ms_dense_step / full_ms, 8), "unit": out["unit"], "cores": oracle.num_threads(),
             "kind": "oracle",
             "sample": f"fp64 oracle (literal Eq. 2 forward + chain-rule backward, gcc -O2 OpenMP) on the "
-                      f"m=k=n={sm}, r={r} sub-problem: {dt:.2f} s; scaled by m*k*n ratio {scale:.0f} to the full "
+                      f"m={2 * sm}, k=n={sm}, r={r} sub-problem: {dt:.2f} s; scaled by m*k*n ratio {scale:.0f} to the full "
                       f"workload = {full_ms / 1e3:.0f} s per step (extrapolated)",
             "oracle_seconds_sample": round(dt, 3),
         }
-        log(f"  cpu oracle: {dt:.2f} s on {sm}^3 sample with {oracle.num_threads()} threads")
+        log(f"  cpu oracle: {dt:.2f} s on {2 * sm}x{sm}x{sm} sample with {oracle.num_threads()} threads")
 
     print(json.dumps(out), flush=True)
 

@@ -225,10 +225,14 @@ __global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restric
 #pragma unroll
     for (int g = 0; g < 4; ++g) acc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    for (long base = t0; base < t1; base += 256) {       // uniform trip count over the block
+    // operands of one 256-tile step of the block: this wavefront's 64 tiles of V (4 rows x 8 bytes per lane) and the
+    // P fragments (8 consecutive tiles of a plane per lane).  The next step's operands are in flight while the
+    // current step runs on the matrix cores.
+    u32x2_t v[4];
+    u32x4_t pa[2][4];
+    auto fetch = [&](long base) {
         const long tb = base + wave * 64;
         const long tile = tb + lane;
-        u32x2_t v[4];
         if (tile < t1) {
             const long I = tile / Cc, J = tile - I * Cc;
 #pragma unroll
@@ -238,26 +242,41 @@ __global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restric
             for (int a = 0; a < 4; ++a) v[a] = u32x2_t{0u, 0u};
         }
 #pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const long tk = tb + 32 * s + 8 * kq;        // 8 consecutive tiles; all inside or all outside (T % 8 == 0)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int pl = 16 * g + q;
+                u32x4_t av = {0u, 0u, 0u, 0u};
+                if (g < ngroups && pl < r && tk < t1) av = *reinterpret_cast<const u32x4_t *>(P + (size_t)pl * T + tk);
+                pa[s][g] = av;
+            }
+        }
+    };
+
+    fetch(t0);
+    for (long base = t0; base < t1; base += 256) {       // uniform trip count over the block
+#pragma unroll
         for (int a = 0; a < 4; ++a) {
             sV[wave][4 * a + 0][lane] = (bf16_t)(v[a][0] & 0xffffu);
             sV[wave][4 * a + 1][lane] = (bf16_t)(v[a][0] >> 16);
             sV[wave][4 * a + 2][lane] = (bf16_t)(v[a][1] & 0xffffu);
             sV[wave][4 * a + 3][lane] = (bf16_t)(v[a][1] >> 16);
         }
+        u32x4_t pc[2][4];
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) pc[s][g] = pa[s][g];
         __syncthreads();
+        if (base + 256 < t1) fetch(base + 256);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const bf16x8_t fb = *reinterpret_cast<const bf16x8_t *>(&sV[wave][q][32 * s + 8 * kq]);
-            const long tk = tb + 32 * s + 8 * kq;        // 8 consecutive tiles; all inside or all outside (T % 8 == 0)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                if (g < ngroups) {
-                    const int pl = 16 * g + q;
-                    u32x4_t av = {0u, 0u, 0u, 0u};
-                    if (pl < r && tk < t1) av = *reinterpret_cast<const u32x4_t *>(P + (size_t)pl * T + tk);
-                    acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av), fb, acc[g], 0, 0, 0);
-                }
-            }
+            for (int g = 0; g < 4; ++g)
+                if (g < ngroups)
+                    acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pc[s][g]), fb, acc[g], 0, 0, 0);
         }
         __syncthreads();
     }

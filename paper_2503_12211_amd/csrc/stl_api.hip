@@ -102,9 +102,12 @@ BwdWs bwd_layout(const Dims &d)
     off += pk;
     w.yhat = off;
     off += pn;
-    const int nb_n = stl::outer_reduce_blocks((int64_t)d.M * d.N), nb_k = stl::outer_reduce_blocks((int64_t)d.M * d.K);
+    int nb = stl::outer_reduce_blocks((int64_t)d.M * d.N);
+    const int nb_k = stl::outer_reduce_blocks((int64_t)d.M * d.K), nb_f = stl::decode_outer_blocks(d.M, d.K);
+    nb = nb > nb_k ? nb : nb_k;
+    nb = nb > nb_f ? nb : nb_f;
     w.part = off;
-    off += align256((size_t)(nb_n > nb_k ? nb_n : nb_k) * d.r * 16 * sizeof(float));
+    off += align256((size_t)nb * d.r * 16 * sizeof(float));
     w.total = off;
     return w;
 }
@@ -282,8 +285,14 @@ stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *
         stl::GemmDesc g{d.K, d.N, d.M, d.r, true, true, true, accumulate != 0};
         STL_HIP(stl::launch_plane_gemm(dt, g, xhat, dyhat, dWhat, s), "backward/dWhat");
     }
-    if (dX) STL_HIP(stl::launch_decode(dt, dxhat, E_X, dX, d.M, d.K, d.r, false, s), "backward/decode dX");
-    if (dE_X) STL_HIP(stl::launch_outer_reduce(dt, dxhat, X, dE_X, part, d.M, d.K, d.r, accumulate, s), "backward/dE_X");
+    if (dX && dE_X && stl::decode_outer_eligible(dt, d.K)) {
+        // one pass over dXhat: dX = decode with E_X, dE_X = sum over tiles of dXhat (x) x
+        STL_HIP(stl::launch_decode_outer(dxhat, E_X, dX, X, dE_X, part, d.M, d.K, d.r, accumulate, s), "backward/dX + dE_X");
+    } else {
+        if (dX) STL_HIP(stl::launch_decode(dt, dxhat, E_X, dX, d.M, d.K, d.r, false, s), "backward/decode dX");
+        if (dE_X)
+            STL_HIP(stl::launch_outer_reduce(dt, dxhat, X, dE_X, part, d.M, d.K, d.r, accumulate, s), "backward/dE_X");
+    }
     return STL_OK;
 }
 

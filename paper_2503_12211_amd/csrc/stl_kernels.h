@@ -18,6 +18,13 @@ int outer_reduce_blocks(int64_t tiles);
 hipError_t launch_outer_reduce(int dtype, const void *P, const void *V, float *G, float *part, int R, int Cc, int r,
                                int accumulate, hipStream_t s);
 
+// decode and basis gradient in one pass over the planes (bf16): Cmat <- decode(P, Dm), G (+)= P . tileview(V);
+// `part` holds decode_outer_blocks(R, Cc) * r * 16 floats
+bool decode_outer_eligible(int dtype, int Cc);
+int decode_outer_blocks(int R, int Cc);
+hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const void *V, float *G, float *part, int R,
+                               int Cc, int r, int accumulate, hipStream_t s);
+
 // Batched plane products  Out[p][i][j] (+)= sum_l A[p](i,l) * B[p](l,j),  p < batch, dense planes.
 struct GemmDesc {
     int Mi, Nj, Kl;   // output rows, output columns, contraction length (all in tiles of the STL problem)

@@ -300,12 +300,22 @@ __global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restric
 // ---------------------------------------------------------------------------------------
 typedef short v4i16_t __attribute__((ext_vector_type(4)));
 
-template <bool GELU, int KC>   // KC = number of 32-plane groups (1: r <= 32, 2: r <= 64)
+// OUTER: the same pass also accumulates the basis gradient G (r x 16) += P (r x tiles) . tileview(V) (tiles x 16)
+// (dE_X with P = dXhat, V = X while dX is decoded), so that the planes are read from HBM once for both results;
+// every block writes one partial to `part`, added up in block order by outer_final_kernel.
+template <bool GELU, int KC, bool OUTER>   // KC = number of 32-plane groups (1: r <= 32, 2: r <= 64)
 __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restrict__ P, const bf16_t *__restrict__ Dm,
-                                                          bf16_t *__restrict__ Cmat, int R, int Cc, int r, int chunks)
+                                                          bf16_t *__restrict__ Cmat, int R, int Cc, int r, int chunks,
+                                                          const bf16_t *__restrict__ V, float *__restrict__ part)
 {
     constexpr int ROWB = 128;                               // bytes per LDS row (64 tiles)
+    constexpr int VPITCH = 64 + 8;                          // bf16 elements per row of the entry x tile staging
     __shared__ __align__(16) char slab_all[4][KC * 32 * ROWB];
+    __shared__ __align__(16) bf16_t sV[OUTER ? 4 : 1][OUTER ? 16 : 1][OUTER ? VPITCH : 8];
+    const int ngroups = (r + 15) >> 4;
+    f32x4_t oacc[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) oacc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     char *slab = slab_all[wave];
     const int j = lane & 15, kq = lane >> 4;
@@ -350,8 +360,37 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
                     *reinterpret_cast<u32x4_t *>(slab + pl * ROWB + ((ch ^ swz(pl)) << 4)) = v;
                 }
             }
+            if (OUTER) {
+                // lane = tile J0 + lane: its 16 entries (4 rows x 8 bytes) -> sV[entry][tile]
+                const int Jt = J0 + lane;
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    u32x2_t xv = {0u, 0u};
+                    if (Jt < Cc) xv = *reinterpret_cast<const u32x2_t *>(V + ((size_t)I * 4 + a) * ld + (size_t)Jt * 4);
+                    sV[wave][4 * a + 0][lane] = (bf16_t)(xv[0] & 0xffffu);
+                    sV[wave][4 * a + 1][lane] = (bf16_t)(xv[0] >> 16);
+                    sV[wave][4 * a + 2][lane] = (bf16_t)(xv[1] & 0xffffu);
+                    sV[wave][4 * a + 3][lane] = (bf16_t)(xv[1] >> 16);
+                }
+            }
         }
         __syncthreads();
+        if (live && OUTER) {
+            // K = 32 tiles per MFMA: A = planes x tiles from the slab (lane: plane 16g + j, tiles 32s + 8kq ..),
+            // B = tiles x entries from sV (lane: entry j, same tiles)
+#pragma unroll
+            for (int sx = 0; sx < 2; ++sx) {
+                const bf16x8_t fb = *reinterpret_cast<const bf16x8_t *>(&sV[wave][j][32 * sx + 8 * kq]);
+#pragma unroll
+                for (int g = 0; g < 2 * KC; ++g) {
+                    if (g < ngroups) {
+                        const int pl = 16 * g + j;
+                        const bf16x8_t fp = *reinterpret_cast<const bf16x8_t *>(slab + pl * ROWB + (((4 * sx + kq) ^ swz(pl)) << 4));
+                        oacc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fp, fb, oacc[g], 0, 0, 0);
+                    }
+                }
+            }
+        }
         if (live) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {                   // 16 tiles per MFMA
@@ -381,6 +420,18 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
                 }
             }
         }
+    }
+    if (OUTER) {
+        // accumulator e of group g: plane 16g + 4*kq + e, tile entry j; fixed-order sum over the four wavefronts
+        __syncthreads();
+        float *red = reinterpret_cast<float *>(&slab_all[0][0]);      // 4 x (64 x 16) floats fit in the slabs
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) red[wave * 1024 + (16 * g + 4 * kq + e) * 16 + j] = oacc[g][e];
+        __syncthreads();
+        for (int i = threadIdx.x; i < r * 16; i += 256)
+            part[(size_t)blockIdx.x * r * 16 + i] = ((red[i] + red[1024 + i]) + red[2048 + i]) + red[3072 + i];
     }
 }
 
@@ -431,16 +482,43 @@ hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, i
         const bf16_t *p = (const bf16_t *)P, *d = (const bf16_t *)Dm;
         bf16_t *c = (bf16_t *)Cmat;
         if (r <= 32) {
-            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 1>), grid, block, 0, s, p, d, c, R, Cc, r, chunks);
-            else hipLaunchKernelGGL((decode_mfma_kernel<false, 1>), grid, block, 0, s, p, d, c, R, Cc, r, chunks);
+            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 1, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr);
+            else hipLaunchKernelGGL((decode_mfma_kernel<false, 1, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr);
         } else {
-            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 2>), grid, block, 0, s, p, d, c, R, Cc, r, chunks);
-            else hipLaunchKernelGGL((decode_mfma_kernel<false, 2>), grid, block, 0, s, p, d, c, R, Cc, r, chunks);
+            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 2, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr);
+            else hipLaunchKernelGGL((decode_mfma_kernel<false, 2, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr);
         }
         return hipGetLastError();
     }
     return dtype == 0 ? launch_decode_t<float>(P, Dm, Cmat, R, Cc, r, gelu, s)
                       : launch_decode_t<bf16_t>(P, Dm, Cmat, R, Cc, r, gelu, s);
+}
+
+bool decode_outer_eligible(int dtype, int Cc) { return dtype == 1 && (Cc % 8) == 0; }
+
+int decode_outer_blocks(int R, int Cc)
+{
+    const long items = (long)R * ((Cc + 63) / 64);
+    const long blocks = (items + 3) / 4;
+    return (int)(blocks > 1024 ? 1024 : blocks);
+}
+
+hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const void *V, float *G, float *part, int R,
+                               int Cc, int r, int accumulate, hipStream_t s)
+{
+    const int chunks = (Cc + 63) / 64;
+    const int nb = decode_outer_blocks(R, Cc);
+    const bf16_t *p = (const bf16_t *)P, *d = (const bf16_t *)Dm, *v = (const bf16_t *)V;
+    bf16_t *c = (bf16_t *)Cmat;
+    if (r <= 32)
+        hipLaunchKernelGGL((decode_mfma_kernel<false, 1, true>), dim3(nb), dim3(256), 0, s, p, d, c, R, Cc, r, chunks, v, part);
+    else
+        hipLaunchKernelGGL((decode_mfma_kernel<false, 2, true>), dim3(nb), dim3(256), 0, s, p, d, c, R, Cc, r, chunks, v, part);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int n_out = r * 16;
+    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 15) / 16), dim3(256), 0, s, part, G, nb, n_out, accumulate);
+    return hipGetLastError();
 }
 
 static int outer_tiles_per_block(int64_t tiles)

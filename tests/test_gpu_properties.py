@@ -1,0 +1,51 @@
+"""Property tests on the GPU path (random small shapes): parity with the oracle, bilinearity, rank additivity."""
+import numpy as np
+import pytest
+
+import oracle
+import stl_synth
+
+hyp = pytest.importorskip("hypothesis")
+from hypothesis import given, settings, strategies as st, HealthCheck
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+    return gpu_util
+
+
+dims = st.integers(min_value=1, max_value=24).map(lambda v: 4 * v)
+
+
+@settings(max_examples=25, deadline=None, suppress_health_check=[HealthCheck.function_scoped_fixture])
+@given(m=dims, k=dims, n=dims, r=st.integers(1, 64), seed=st.integers(0, 2 ** 16), dtype=st.sampled_from(["f32", "bf16"]))
+def test_forward_backward_random_shapes(gu, m, k, n, r, seed, dtype):
+    p = stl_synth.stl_problem(m, k, n, r, seed=seed, dtype=dtype, with_dC=True)
+    C = gu.forward(p, dtype)
+    assert gu.rel(C, oracle.forward(p["X"], p["What"], p["E_X"], p["D"])) <= gu.TOL[dtype]
+    got = gu.backward(p, dtype)
+    ref = oracle.backward(p["X"], p["What"], p["E_X"], p["D"], p["dC"])
+    for name, g in zip(("dX", "dWhat", "dE_X", "dD"), ref):
+        assert gu.rel(got[name], g) <= gu.TOL[dtype], name
+
+
+def test_fp32_bilinearity_and_rank_additivity(gu):
+    """fp32 path: f(aX1+bX2) = a f(X1) + b f(X2); planes [0,r1) plus planes [r1,r) add up to all planes."""
+    rng = np.random.default_rng(5)
+    p = stl_synth.stl_problem(64, 96, 128, 24, seed=9, dtype="f32")
+    X2 = rng.standard_normal(p["X"].shape).astype(np.float32)
+    q = dict(p)
+    q["X"] = (0.5 * p["X"] - 2.0 * X2).astype(np.float32)
+    q2 = dict(p)
+    q2["X"] = X2
+    lhs = gu.forward(q, "f32")
+    rhs = 0.5 * gu.forward(p, "f32") - 2.0 * gu.forward(q2, "f32")
+    assert gu.rel(lhs, rhs) <= 1e-5
+    part = 0
+    for sl in (slice(0, 10), slice(10, 24)):
+        s = {"X": p["X"], "What": p["What"][sl], "E_X": p["E_X"][sl], "D": p["D"][sl]}
+        part = part + gu.forward(s, "f32")
+    assert gu.rel(part, gu.forward(p, "f32")) <= 1e-5

@@ -82,7 +82,22 @@ def gelu(h):
     return 0.5 * h * (1.0 + erf(h / np.sqrt(2.0)))
 
 
-def mlp_pair(X, What1, E_X1, D1, What2, E_X2, D2, t: int = 4):
-    """STL up-projection, GELU, STL down-projection; fp64 end to end."""
-    H = gelu(forward(X, What1, E_X1, D1, t))
-    return forward(H, What2, E_X2, D2, t)
+def recode(Yhat, D, E_next, activation: str | None = "gelu", t: int = 4):
+    """Inter-layer step of Algorithm 2 (its Steps 3 and 1 taken together): decode the encoded output of
+    one layer with D, apply the activation entrywise (``None``: the paper's purely linear case, where the
+    step collapses to one (r_next x r) map per tile), encode the result with the next layer's E_X.
+    Output tile (I, J) of the first layer is input tile (I, L = J) of the second."""
+    H = decode(Yhat, D, t)
+    if activation == "gelu":
+        H = gelu(H)
+    elif activation is not None:
+        raise ValueError("activation must be 'gelu' or None")
+    return encode(H, E_next, t)
+
+
+def mlp_pair(X, What1, E_X1, D1, What2, E_X2, D2, t: int = 4, activation: str | None = "gelu"):
+    """STL up-projection, activation (exact GELU, or none), STL down-projection; fp64 end to end.
+    Written as Algorithm 2 does it: the hidden activation only exists between decode and encode."""
+    Yhat1 = plane_products(encode(X, E_X1, t), What1)
+    Xhat2 = recode(Yhat1, D1, E_X2, activation, t)
+    return decode(plane_products(Xhat2, What2), D2, t)

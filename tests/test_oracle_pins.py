@@ -277,6 +277,47 @@ def test_algorithm2_fused_decode_encode_identity():
     assert rel(enc_of_dec, direct) < 1e-13
 
 
+def test_recode_is_decode_activation_encode():
+    """The inter-layer step against its parts: linear case = one (r2 x r1) map per tile (Algorithm 2);
+    GELU case = entrywise GELU of the decoded tiles, checked entry by entry with math.erf."""
+    import math
+    r1, r2 = 7, 5
+    Y = RNG.standard_normal((r1, 3, 4))
+    D = RNG.standard_normal((r1, 16))
+    E = RNG.standard_normal((r2, 16))
+    lin = planes.recode(Y, D, E, activation=None)
+    assert rel(lin, np.einsum("pIJ,sp->sIJ", Y, E @ D.T)) < 1e-13
+    got = planes.recode(Y, D, E, activation="gelu")
+    want = np.zeros((r2, 3, 4))
+    for I in range(3):
+        for J in range(4):
+            h = [sum(D[p, q] * Y[p, I, J] for p in range(r1)) for q in range(16)]
+            g = [0.5 * v * (1.0 + math.erf(v / math.sqrt(2.0))) for v in h]
+            for s_ in range(r2):
+                want[s_, I, J] = sum(E[s_, q] * g[q] for q in range(16))
+    assert rel(got, want) < 1e-13
+    with pytest.raises(ValueError):
+        planes.recode(Y, D, E, activation="relu")
+
+
+@pytest.mark.parametrize("basis", ["strassen", "trivial"])
+def test_mlp_pair_at_exact_bases_is_textbook_mlp(basis):
+    """With exact bases in both layers the pair equals act(X W1) W2 computed with plain matrix products."""
+    E_X, E_W, D = bases.strassen_4x4() if basis == "strassen" else bases.trivial(4)
+    m, d, h = 8, 12, 16
+    X = RNG.standard_normal((m, d))
+    W1 = RNG.standard_normal((d, h)) / np.sqrt(d)
+    W2 = RNG.standard_normal((h, d)) / np.sqrt(h)
+    Wh1, Wh2 = oracle.encode_weight(W1, E_W), oracle.encode_weight(W2, E_W)
+    lin = planes.mlp_pair(X, Wh1, E_X, D, Wh2, E_X, D, activation=None)
+    assert rel(lin, X @ W1 @ W2) < 1e-12
+    act = planes.mlp_pair(X, Wh1, E_X, D, Wh2, E_X, D)
+    assert rel(act, planes.gelu(X @ W1) @ W2) < 1e-12
+    # and the pair is the composition of two single-layer forwards of the tile-by-tile oracle
+    two = oracle.forward(planes.gelu(oracle.forward(X, Wh1, E_X, D)), Wh2, E_X, D)
+    assert rel(act, two) < 1e-12
+
+
 def test_gelu_values():
     """Exact-erf GELU against closed-form values: gelu(0)=0, gelu(x)-gelu(-x)=x, gelu(1)=Phi(1)."""
     assert planes.gelu(0.0) == 0.0

@@ -127,6 +127,36 @@ stl_status_t stl_plane_matmul(const stl_problem_t *prob, const void *Xhat, const
 stl_status_t stl_decode(const stl_problem_t *prob, const void *Yhat, const void *D, void *C,
                         int flags, void *stream);
 
+/*
+ * Two stacked STL layers, C = (act(X <> W1)) <> W2 (Algorithm 2; Section "Strassen-Tile Operator",
+ * paragraph on fusing step (iii) of one layer with step (i) of the next).  `up` describes the first
+ * layer (X m x k1 -> n1), `down` the second (m x k2 -> n2) with down.m == up.m, down.k == up.n, same t
+ * and dtype; the ranks may differ.  Output tile (I,J) of the first layer is input tile (I,L=J) of the
+ * second, so decode, activation and the next encode are done per tile in one pass over the planes and
+ * the hidden activation (m x n1) is never written:
+ *     Xhat2[s][I][J] = sum_q E_X2[s][q] act( sum_p D1[p][q] Yhat1[p][I][J] ).
+ * flags: STL_FLAG_GELU applies the exact-erf GELU between the layers (evaluated in fp32, rounded to
+ *   the storage dtype before the second encode); without it the step is the paper's linear map
+ *   Yhat1 (D1 E_X2^T) per tile.  Variant STL_FLAG_AUTO uses the one-pass step where its kernel
+ *   applies (bf16, n1/4 a multiple of 8); STL_FLAG_UNFUSED always runs decode and encode as two
+ *   launches through a hidden-activation buffer in the workspace.  Other variant values: UNSUPPORTED.
+ * X: m x k1 (in).  What1: r1 x K1 x N1, What2: r2 x N1 x N2 (in).  E_X1, D1: r1 x 16; E_X2, D2: r2 x 16 (in).
+ * C: m x n2 (out).  ws / ws_bytes: at least stl_mlp_workspace_bytes(up, down, flags).
+ */
+size_t stl_mlp_workspace_bytes(const stl_problem_t *up, const stl_problem_t *down, int flags);
+stl_status_t stl_mlp_forward(const stl_problem_t *up, const stl_problem_t *down, const void *X,
+                             const void *What1, const void *E_X1, const void *D1, const void *What2,
+                             const void *E_X2, const void *D2, void *C, void *ws, size_t ws_bytes,
+                             int flags, void *stream);
+/*
+ * The inter-layer step of stl_mlp_forward on its own: Yhat1 r1 x M x N1 (in), D1 r1 x 16, E_X2 r2 x 16
+ * (in) -> Xhat2 r2 x M x N1 (out).  H: scratch for the hidden activation, m x n1 elements of the storage
+ * dtype; may be NULL when the one-pass kernel applies (bf16 and n1/4 a multiple of 8) and the variant is
+ * STL_FLAG_AUTO, required otherwise (INVALID_ARG if missing).  flags as for stl_mlp_forward.
+ */
+stl_status_t stl_recode(const stl_problem_t *up, const stl_problem_t *down, const void *Yhat1,
+                        const void *D1, const void *E_X2, void *Xhat2, void *H, int flags, void *stream);
+
 /* Static text for a status code. */
 const char *stl_status_string(stl_status_t status);
 /* Text of the last error raised on the calling thread ("" if none).  Thread-local storage. */

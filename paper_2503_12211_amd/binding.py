@@ -20,7 +20,8 @@ STL_FLAG_GELU = 0x100
 # every symbol include/stl.h declares
 SYMBOLS = (
     "stl_workspace_bytes", "stl_encode_weight", "stl_forward", "stl_backward", "stl_encode_activation",
-    "stl_plane_matmul", "stl_decode", "stl_status_string", "stl_last_error", "stl_version",
+    "stl_plane_matmul", "stl_decode", "stl_mlp_workspace_bytes", "stl_mlp_forward", "stl_recode",
+    "stl_status_string", "stl_last_error", "stl_version",
 )
 
 
@@ -73,8 +74,12 @@ def _load():
     lib.stl_encode_activation.argtypes = [pp, _P, _P, _P, _P]
     lib.stl_plane_matmul.argtypes = [pp, _P, _P, _P, _P]
     lib.stl_decode.argtypes = [pp, _P, _P, _P, ctypes.c_int, _P]
+    lib.stl_mlp_workspace_bytes.restype = ctypes.c_size_t
+    lib.stl_mlp_workspace_bytes.argtypes = [pp, pp, ctypes.c_int]
+    lib.stl_mlp_forward.argtypes = [pp, pp, _P, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, ctypes.c_int, _P]
+    lib.stl_recode.argtypes = [pp, pp, _P, _P, _P, _P, _P, ctypes.c_int, _P]
     for name in ("stl_encode_weight", "stl_forward", "stl_backward", "stl_encode_activation", "stl_plane_matmul",
-                 "stl_decode"):
+                 "stl_decode", "stl_mlp_forward", "stl_recode"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stl_status_string.restype = ctypes.c_char_p
     lib.stl_status_string.argtypes = [ctypes.c_int]
@@ -155,3 +160,20 @@ def stl_plane_matmul(prob: Problem, Xhat, What, Yhat, stream=None) -> None:
 
 def stl_decode(prob: Problem, Yhat, D, C, flags: int = 0, stream=None) -> None:
     _check(_load().stl_decode(ctypes.byref(prob.c()), _ptr(Yhat), _ptr(D), _ptr(C), flags, _stream(stream)))
+
+
+def stl_mlp_workspace_bytes(up: Problem, down: Problem, flags: int = 0) -> int:
+    return int(_load().stl_mlp_workspace_bytes(ctypes.byref(up.c()), ctypes.byref(down.c()), flags))
+
+
+def stl_mlp_forward(up: Problem, down: Problem, X, What1, E_X1, D1, What2, E_X2, D2, C, ws=None, ws_bytes: int = 0,
+                    flags: int = STL_FLAG_AUTO, stream=None) -> None:
+    _check(_load().stl_mlp_forward(ctypes.byref(up.c()), ctypes.byref(down.c()), _ptr(X), _ptr(What1), _ptr(E_X1),
+                                   _ptr(D1), _ptr(What2), _ptr(E_X2), _ptr(D2), _ptr(C), _ptr(ws), ws_bytes, flags,
+                                   _stream(stream)))
+
+
+def stl_recode(up: Problem, down: Problem, Yhat1, D1, E_X2, Xhat2, H=None, flags: int = STL_FLAG_AUTO,
+               stream=None) -> None:
+    _check(_load().stl_recode(ctypes.byref(up.c()), ctypes.byref(down.c()), _ptr(Yhat1), _ptr(D1), _ptr(E_X2),
+                              _ptr(Xhat2), _ptr(H), flags, _stream(stream)))

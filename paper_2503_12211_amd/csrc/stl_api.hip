@@ -112,6 +112,55 @@ BwdWs bwd_layout(const Dims &d)
     return w;
 }
 
+struct MlpWs {
+    size_t xhat1, yhat1, xhat2, yhat2, hidden, total;
+    bool one_pass;
+};
+
+// the two layers must chain: same rows, up.n == down.k, same tile size and storage type
+stl_status_t check_pair(const stl_problem_t *up, const stl_problem_t *down, Dims *d1, Dims *d2)
+{
+    stl_status_t st = check_problem(up, d1);
+    if (st != STL_OK) return st;
+    st = check_problem(down, d2);
+    if (st != STL_OK) return st;
+    if (up->m != down->m || up->n != down->k)
+        return fail(STL_ERR_INVALID_ARG, "layers do not chain: up is %lld x %lld -> %lld, down is %lld x %lld -> %lld",
+                    (long long)up->m, (long long)up->k, (long long)up->n, (long long)down->m, (long long)down->k,
+                    (long long)down->n);
+    if (up->dtype != down->dtype) return fail(STL_ERR_INVALID_ARG, "layers differ in dtype");
+    return STL_OK;
+}
+
+stl_status_t check_pair_flags(int flags, int *variant)
+{
+    if (flags & ~(STL_FLAG_VARIANT_MASK | STL_FLAG_GELU)) return fail(STL_ERR_UNSUPPORTED, "unknown flag bits 0x%x", flags);
+    const int v = variant_of(flags);
+    if (v != STL_FLAG_AUTO && v != STL_FLAG_UNFUSED)
+        return fail(STL_ERR_UNSUPPORTED, "layer pair: variant %d is not available (AUTO or UNFUSED)", v);
+    *variant = v;
+    return STL_OK;
+}
+
+MlpWs mlp_layout(const stl_problem_t *up, const Dims &d1, const Dims &d2, int variant)
+{
+    MlpWs w{};
+    size_t off = 0;
+    w.xhat1 = off;
+    off += align256((size_t)d1.r * d1.M * d1.K * d1.es);
+    w.yhat1 = off;
+    off += align256((size_t)d1.r * d1.M * d1.N * d1.es);
+    w.xhat2 = off;
+    off += align256((size_t)d2.r * d2.M * d2.K * d2.es);
+    w.yhat2 = off;
+    off += align256((size_t)d2.r * d2.M * d2.N * d2.es);
+    w.one_pass = variant == STL_FLAG_AUTO && stl::recode_eligible(up->dtype, d1.N);
+    w.hidden = off;
+    if (!w.one_pass) off += align256((size_t)up->m * up->n * d1.es);
+    w.total = off;
+    return w;
+}
+
 #define STL_HIP(call, what)                                \
     do {                                                   \
         hipError_t e__ = (call);                           \
@@ -293,6 +342,74 @@ stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *
         if (dE_X)
             STL_HIP(stl::launch_outer_reduce(dt, dxhat, X, dE_X, part, d.M, d.K, d.r, accumulate, s), "backward/dE_X");
     }
+    return STL_OK;
+}
+
+size_t stl_mlp_workspace_bytes(const stl_problem_t *up, const stl_problem_t *down, int flags)
+{
+    Dims d1, d2;
+    int v;
+    if (check_pair(up, down, &d1, &d2) != STL_OK || check_pair_flags(flags, &v) != STL_OK) return 0;
+    return mlp_layout(up, d1, d2, v).total;
+}
+
+stl_status_t stl_recode(const stl_problem_t *up, const stl_problem_t *down, const void *Yhat1, const void *D1,
+                        const void *E_X2, void *Xhat2, void *H, int flags, void *stream)
+{
+    Dims d1, d2;
+    stl_status_t st = check_pair(up, down, &d1, &d2);
+    if (st != STL_OK) return st;
+    int variant;
+    st = check_pair_flags(flags, &variant);
+    if (st != STL_OK) return st;
+    if (!Yhat1 || !D1 || !E_X2 || !Xhat2) return fail(STL_ERR_INVALID_ARG, "stl_recode: NULL pointer");
+    hipStream_t s = (hipStream_t)stream;
+    const bool gelu = (flags & STL_FLAG_GELU) != 0;
+    if (variant == STL_FLAG_AUTO && stl::recode_eligible(up->dtype, d1.N)) {
+        STL_HIP(stl::launch_recode(Yhat1, D1, E_X2, Xhat2, d1.M, d1.N, d1.r, d2.r, gelu, s), "recode");
+        return STL_OK;
+    }
+    if (!H) return fail(STL_ERR_INVALID_ARG, "stl_recode: the two-launch form needs the hidden-activation scratch H");
+    STL_HIP(stl::launch_decode(up->dtype, Yhat1, D1, H, d1.M, d1.N, d1.r, gelu, s), "recode/decode");
+    STL_HIP(stl::launch_encode(up->dtype, H, E_X2, Xhat2, d2.M, d2.K, d2.r, s), "recode/encode");
+    return STL_OK;
+}
+
+stl_status_t stl_mlp_forward(const stl_problem_t *up, const stl_problem_t *down, const void *X, const void *What1,
+                             const void *E_X1, const void *D1, const void *What2, const void *E_X2, const void *D2,
+                             void *C, void *ws, size_t ws_bytes, int flags, void *stream)
+{
+    Dims d1, d2;
+    stl_status_t st = check_pair(up, down, &d1, &d2);
+    if (st != STL_OK) return st;
+    int variant;
+    st = check_pair_flags(flags, &variant);
+    if (st != STL_OK) return st;
+    if (!X || !What1 || !E_X1 || !D1 || !What2 || !E_X2 || !D2 || !C)
+        return fail(STL_ERR_INVALID_ARG, "stl_mlp_forward: NULL pointer");
+    const MlpWs w = mlp_layout(up, d1, d2, variant);
+    if (!ws || ws_bytes < w.total)
+        return fail(STL_ERR_WORKSPACE, "stl_mlp_forward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
+    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_mlp_forward: workspace is not 16-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    const int dt = up->dtype;
+    const bool gelu = (flags & STL_FLAG_GELU) != 0;
+    char *base = (char *)ws;
+    void *xhat1 = base + w.xhat1, *yhat1 = base + w.yhat1, *xhat2 = base + w.xhat2, *yhat2 = base + w.yhat2;
+
+    STL_HIP(stl::launch_encode(dt, X, E_X1, xhat1, d1.M, d1.K, d1.r, s), "pair/encode");
+    stl::GemmDesc g1{d1.M, d1.N, d1.K, d1.r, false, true, false, false};
+    STL_HIP(stl::launch_plane_gemm(dt, g1, xhat1, What1, yhat1, s), "pair/plane products 1");
+    if (w.one_pass) {
+        STL_HIP(stl::launch_recode(yhat1, D1, E_X2, xhat2, d1.M, d1.N, d1.r, d2.r, gelu, s), "pair/decode-activation-encode");
+    } else {
+        void *hid = base + w.hidden;
+        STL_HIP(stl::launch_decode(dt, yhat1, D1, hid, d1.M, d1.N, d1.r, gelu, s), "pair/decode 1");
+        STL_HIP(stl::launch_encode(dt, hid, E_X2, xhat2, d2.M, d2.K, d2.r, s), "pair/encode 2");
+    }
+    stl::GemmDesc g2{d2.M, d2.N, d2.K, d2.r, false, true, false, false};
+    STL_HIP(stl::launch_plane_gemm(dt, g2, xhat2, What2, yhat2, s), "pair/plane products 2");
+    STL_HIP(stl::launch_decode(dt, yhat2, D2, C, d2.M, d2.N, d2.r, false, s), "pair/decode 2");
     return STL_OK;
 }
 

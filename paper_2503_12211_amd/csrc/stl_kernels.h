@@ -25,6 +25,12 @@ int decode_outer_blocks(int R, int Cc);
 hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const void *V, float *G, float *part, int R,
                                int Cc, int r, int accumulate, hipStream_t s);
 
+// inter-layer step of two stacked layers in one pass (bf16): Q[s] <- encode_{E2}( act( decode_{Dm}(P) ) ), planes P
+// r1 x R x Cc -> planes Q r2 x R x Cc, the hidden activation never stored
+bool recode_eligible(int dtype, int Cc);
+hipError_t launch_recode(const void *P, const void *Dm, const void *E2, void *Q, int R, int Cc, int r1, int r2, bool gelu,
+                         hipStream_t s);
+
 // Batched plane products  Out[p][i][j] (+)= sum_l A[p](i,l) * B[p](l,j),  p < batch, dense planes.
 struct GemmDesc {
     int Mi, Nj, Kl;   // output rows, output columns, contraction length (all in tiles of the STL problem)

@@ -70,3 +70,35 @@ def backward(p, dtype, yhat=None, accumulate=0, init=None, skip=(), xhat=None):
                      accumulate, ws, nbytes)
     torch.cuda.synchronize()
     return {k_: host(v) for k_, v in outs.items()}
+
+
+def mlp_forward(p1, p2, dtype, flags=0):
+    """p1, p2: dicts with What, E_X, D of the two layers (p1 also X).  Returns C of the pair as float64 numpy."""
+    m, k1 = p1["X"].shape
+    r1, _, N1 = p1["What"].shape
+    r2, K2, N2 = p2["What"].shape
+    assert K2 == N1
+    up = stl.Problem(m, k1, 4 * N1, r1, STL_DT[dtype])
+    down = stl.Problem(m, 4 * K2, 4 * N2, r2, STL_DT[dtype])
+    X, W1, E1, D1 = (dev(p1[s], dtype) for s in ("X", "What", "E_X", "D"))
+    W2, E2, D2 = (dev(p2[s], dtype) for s in ("What", "E_X", "D"))
+    C = torch.full((m, 4 * N2), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
+    nbytes = stl.stl_mlp_workspace_bytes(up, down, flags)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    stl.stl_mlp_forward(up, down, X, W1, E1, D1, W2, E2, D2, C, ws, nbytes, flags)
+    torch.cuda.synchronize()
+    return host(C)
+
+
+def recode(Yhat1, D1, E2, dtype, flags=0, with_scratch=False):
+    """Inter-layer step on its own: Yhat1 (r1, M, N1) -> Xhat2 (r2, M, N1) as float64 numpy."""
+    r1, M, N1 = Yhat1.shape
+    r2 = E2.shape[0]
+    up = stl.Problem(4 * M, 4, 4 * N1, r1, STL_DT[dtype])          # k of the first layer plays no part in this step
+    down = stl.Problem(4 * M, 4 * N1, 4, r2, STL_DT[dtype])
+    Y, D, E = dev(Yhat1, dtype), dev(D1, dtype), dev(E2, dtype)
+    Xh2 = torch.full((r2, M, N1), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
+    H = torch.empty((4 * M, 4 * N1), dtype=TORCH_DT[dtype], device="cuda") if with_scratch else None
+    stl.stl_recode(up, down, Y, D, E, Xh2, H, flags)
+    torch.cuda.synchronize()
+    return host(Xh2)

@@ -92,3 +92,38 @@ def test_block_resident_variants_reject_unsupported_shapes():
         stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, 1 << 40, stl.STL_FLAG_FUSED, stream=0)
     assert e.value.status == 2
     assert stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD, stl.STL_FLAG_FUSED) == 0
+
+
+def test_layer_pair_argument_checks():
+    """stl_mlp_forward / stl_recode: chaining, variant, pointer and workspace checks happen before any launch."""
+    up = stl.Problem(512, 256, 1024, 24, stl.STL_BF16)
+    down = stl.Problem(512, 1024, 256, 16, stl.STL_BF16)
+    need = stl.stl_mlp_workspace_bytes(up, down, 0)
+    planes = 2 * (24 * 128 * 64 + 24 * 128 * 256 + 16 * 128 * 256 + 16 * 128 * 64)
+    assert need == planes
+    # the two-launch form adds the hidden activation
+    assert stl.stl_mlp_workspace_bytes(up, down, stl.STL_FLAG_UNFUSED) == planes + 2 * 512 * 1024
+    # fp32 storage has no one-pass kernel: hidden buffer included
+    up32, down32 = stl.Problem(512, 256, 1024, 24, stl.STL_F32), stl.Problem(512, 1024, 256, 16, stl.STL_F32)
+    assert stl.stl_mlp_workspace_bytes(up32, down32, 0) == 2 * planes + 4 * 512 * 1024
+    args = (FAKE,) * 8
+    for bad_down in (stl.Problem(512, 512, 256, 16), stl.Problem(256, 1024, 256, 16), stl.Problem(512, 1024, 256, 16, stl.STL_F32)):
+        assert stl.stl_mlp_workspace_bytes(up, bad_down, 0) == 0
+        with pytest.raises(stl.StlError) as e:
+            stl.stl_mlp_forward(up, bad_down, *args, FAKE, 1 << 40, 0, stream=0)
+        assert e.value.status == 1
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_mlp_forward(up, down, *args, FAKE, need - 1, 0, stream=0)
+    assert e.value.status == 3
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_mlp_forward(up, down, *args, FAKE, 1 << 40, stl.STL_FLAG_FUSED, stream=0)
+    assert e.value.status == 2
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_mlp_forward(up, down, None, *args[1:], FAKE, 1 << 40, 0, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(stl.StlError) as e:          # two-launch recode without its scratch
+        stl.stl_recode(up, down, FAKE, FAKE, FAKE, FAKE, None, stl.STL_FLAG_UNFUSED, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_recode(up32, down32, FAKE, FAKE, FAKE, FAKE, None, 0, stream=0)
+    assert e.value.status == 1

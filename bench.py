@@ -31,12 +31,14 @@ def log(*a):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C5", help="C5 (default), C2, or m,k,n,r")
     ap.add_argument("--sweep", action="store_true", help="also time the forward r sweep (m=8192,k=n=4096)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--profile-only", default="", help="run only this leg (forward|backward|step|stages|copy) a few times")
+    ap.add_argument("--no-mlp", action="store_true", help="skip the stacked-layer (MLP-shaped pair) leg")
+    ap.add_argument("--profile-only", default="",
+                    help="run only this leg (forward|backward|step|stages|copy|mlp) a few times")
     return ap.parse_args()
 
 
@@ -64,6 +66,27 @@ class Timer:
             fn()
         t.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
+
+    def ramp(self, fn, seconds=0.4):
+        """Untimed: keep the GPU busy until its clocks have ramped up (a cold process measures 15-20 % slow)."""
+        t = self.torch
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(10):
+                fn()
+            t.cuda.synchronize()
+
+    def dist(self, fn, steps):
+        """Per-call durations from one event pair per call: (median, min) in ms."""
+        t = self.torch
+        ev = [(t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        t.cuda.synchronize()
+        d = sorted(a.elapsed_time(b) for a, b in ev)
+        return d[len(d) // 2], d[0]
 
     def events(self, fn, steps, warmup):
         """Average per-launch duration between two events on the current stream (the stream the
@@ -154,6 +177,32 @@ def main():
         fwd()
         bwd()
 
+    def mlp_setup():
+        """MLP-shaped pair of the workload list: m=16384, 1024 -> 4096 -> 1024, r=24, GELU between the layers."""
+        c4 = stl_synth.CONFIGS["C4_up"]
+        mm, d_, h_, rr = c4["m"], c4["k"], c4["n"], c4["r"]
+        q1 = stl_synth.stl_problem(mm, d_, h_, rr, stl_synth.SEEDS["C4_up"], "bf16")
+        q2 = stl_synth.stl_problem(mm, h_, d_, rr, stl_synth.SEEDS["C4_down"], "bf16")
+        up, down = stl.Problem(mm, d_, h_, rr, stl.STL_BF16), stl.Problem(mm, h_, d_, rr, stl.STL_BF16)
+        t1 = [dev(q1[s]) for s in ("X", "What", "E_X", "D")]
+        t2 = [dev(q2[s]) for s in ("What", "E_X", "D")]
+        Cm = torch.empty((mm, d_), dtype=bf, device="cuda")
+        calls = {}
+        for name, fl in (("one_pass", stl.STL_FLAG_GELU), ("two_launch", stl.STL_FLAG_GELU | stl.STL_FLAG_UNFUSED)):
+            nbm = stl.stl_mlp_workspace_bytes(up, down, fl)
+            wsm = torch.empty(nbm, dtype=torch.uint8, device="cuda")
+            calls[name] = (lambda fl=fl, wsm=wsm, nbm=nbm:
+                           stl.stl_mlp_forward(up, down, t1[0], t1[1], t1[2], t1[3], t2[0], t2[1], t2[2], Cm, wsm, nbm, fl))
+        W1 = (torch.randn((d_, h_), device="cuda") * d_ ** -0.5).to(bf)
+        W2 = (torch.randn((h_, d_), device="cuda") * h_ ** -0.5).to(bf)
+        Hd = torch.empty((mm, h_), dtype=bf, device="cuda")
+
+        def dense_pair():
+            torch.matmul(t1[0], W1, out=Hd)
+            torch.matmul(torch.nn.functional.gelu(Hd), W2, out=Cm)
+        calls["dense"] = dense_pair
+        return (mm, d_, h_, rr), calls
+
     if args.profile_only:
         cal_src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda")
         cal_dst = torch.empty_like(cal_src)
@@ -162,6 +211,8 @@ def main():
                 "stages": lambda: (stl.stl_encode_activation(prob, X, E_X, Xhat),
                                    stl.stl_plane_matmul(prob, Xhat, What, Yhat),
                                    stl.stl_decode(prob, Yhat, D, C))}
+        if args.profile_only == "mlp":
+            legs["mlp"] = mlp_setup()[1]["one_pass"]
         fwd()
         for _ in range(max(args.steps, 1)):
             legs[args.profile_only]()
@@ -183,7 +234,9 @@ def main():
         torch.matmul(X.t(), dC, out=dWd)
 
     W, S = args.warmup, args.steps
+    T.ramp(step)
     ms_step = T.wall(step, S, W)
+    step_median, step_min = T.dist(step, min(S, 200))
     ms_dense_step = T.wall(dense_step, S, W)
     ms_fwd = T.wall(fwd_nosave, S, W)
     ms_bwd = T.wall(bwd, S, W)
@@ -217,7 +270,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wname}: STL forward+backward, m={m}, k={k}, n={n}, t=4, r={r}, bf16 in / fp32 accumulate",
                    "m": m, "k": k, "n": n, "t": 4, "r": r},
-        "stl_ms": {"forward": round(ms_fwd, 5), "backward": round(ms_bwd, 5), "step": round(ms_step, 5)},
+        "stl_ms": {"forward": round(ms_fwd, 5), "backward": round(ms_bwd, 5), "step": round(ms_step, 5),
+                   "step_median": round(step_median, 5), "step_min": round(step_min, 5)},
         "dense_ms": {"forward": round(ms_dense_fwd, 5), "step": round(ms_dense_step, 5)},
         "forward_speedup_vs_dense": round(ms_dense_fwd / ms_fwd, 4),
         "stl_tflops_executed": round(tf(fwd_flop + bwd_flop, ms_step), 2),
@@ -248,6 +302,14 @@ def main():
             variants[name] = None
     out["forward_variants_ms"] = variants
     log(f"  forward variants (ms): {variants}")
+
+    if not args.no_mlp:
+        (mm, d_, h_, rr), calls = mlp_setup()
+        pair = {name: round(T.wall(fn, max(S // 2, 2), max(W // 2, 1)), 5) for name, fn in calls.items()}
+        out["mlp_pair"] = {"workload": f"C4: m={mm}, {d_} -> {h_} -> {d_}, r={rr}, GELU between the layers, bf16", "ms": pair,
+                           "speedup_vs_dense": round(pair["dense"] / pair["one_pass"], 4)}
+        log(f"  stacked layers (ms): {pair}")
+        del calls
 
     if args.sweep:
         sweep = {}

@@ -8,9 +8,10 @@
 // 16 tiles, K = planes; a lane (tile, kq) is left with entries 4kq..4kq+3 of its tile.  Rounded to bf16 and
 // padded with four zeros these four values ARE the lane's operand fragment of the second product
 // (rows = tiles, K slot 8kq+e <-> entry 4kq+e for e < 4, zero weight on the other slots), so nothing moves
-// between the two products.  The tiles of decode product u are picked as J0 + 16*(lane/4) + 4u + lane%4;
-// then a lane of the second product (plane, kq) ends up with the 16 consecutive tiles J0 + 16kq ..+15 of
-// its plane: two 16-byte stores, 128 contiguous bytes per plane and wavefront.
+// between the two products.  The tiles of decode product u are picked as J0 + 8*(lane/4) + 4*(u%2) + 32*(u/2) + lane%4;
+// then a lane of the second product (plane, kq) ends up with tiles J0 + 32h + 8kq .. +7 of its plane from
+// products 2h, 2h+1: one 16-byte store each, and the four kq lanes of a plane write 64 contiguous bytes per
+// instruction, 128 per wavefront.
 #include "stl_kernels.h"
 #include "stl_device.h"
 
@@ -25,7 +26,7 @@ __global__ __launch_bounds__(256) void recode_mfma_kernel(const bf16_t *__restri
 {
     constexpr int ROWB = 128;                               // bytes per LDS row (64 tiles)
     __shared__ __align__(16) char slab_all[4][KC * 32 * ROWB];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     char *slab = slab_all[wave];
     const int j = lane & 15, kq = lane >> 4;
     const int ng2 = (r2 + 15) >> 4;
@@ -52,9 +53,6 @@ __global__ __launch_bounds__(256) void recode_mfma_kernel(const bf16_t *__restri
         if (pl < r2) ev = *reinterpret_cast<const u32x2_t *>(E2 + pl * 16 + 4 * kq);
         eb[g2] = __builtin_bit_cast(bf16x8_t, u32x4_t{ev[0], ev[1], 0u, 0u});
     }
-    // rows of planes >= r1 are never loaded: keep them zero (they meet zero D entries, but must be finite)
-    for (int i = lane; i < KC * 32 * ROWB / 16; i += 64) reinterpret_cast<u32x4_t *>(slab)[i] = u32x4_t{0u, 0u, 0u, 0u};
-
     // 16-byte chunk swizzle of a slab row: one transposing read touches rows (planes) that differ in bits 0, 1
     // (lane/4 inside a 16-lane group) and bits 3, 4 (kq), and in each row the chunks 2*(lane%4) + u/2.  Bit 0 of
     // the row already alternates the bank half (128-byte rows); the other three bits shift the chunk index.
@@ -62,25 +60,42 @@ __global__ __launch_bounds__(256) void recode_mfma_kernel(const bf16_t *__restri
 
     const size_t plane = (size_t)R * Cc;
     const long items = (long)R * chunks;
-    for (long item0 = (long)blockIdx.x * 4; item0 < items; item0 += (long)gridDim.x * 4) {
-        const long item = item0 + wave;
-        const bool live = item < items;
-        const int I = live ? (int)(item / chunks) : 0, J0 = live ? (int)(item % chunks) * 64 : 0;
-        __syncthreads();                                    // previous round's fragment reads are done
-        if (live) {
-            // lane -> (plane within group of 8, 16-byte chunk = 8 tiles)
-            const int pr = lane >> 3, ch = lane & 7;
-            const int Jl = J0 + 8 * ch;
+    // (tile row, chunk) of this wavefront's item, advanced without a division per round
+    const long stride = (long)gridDim.x * 4;
+    int In = (int)(((long)blockIdx.x * 4 + wave) / chunks), ckn = (int)(((long)blockIdx.x * 4 + wave) % chunks);
+    const int dI = (int)(stride / chunks), dck = (int)(stride % chunks);
+
+    // lane -> (plane within group of 8, 16-byte chunk = 8 tiles).  The plane segments of the NEXT item are fetched
+    // into registers while the current item is computed and stored, so that a wavefront always has loads in flight.
+    const int pr = lane >> 3, ch = lane & 7;
+    u32x4_t pre[KC * 4];
+    auto fetch = [&](int Ii, int cki) {
+        const int Jl = cki * 64 + 8 * ch;
 #pragma unroll
-            for (int g8 = 0; g8 < KC * 4; ++g8) {
-                const int pl = 8 * g8 + pr;
-                if (pl < r1 && Jl < Cc) {
-                    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(P + (size_t)pl * plane + (size_t)I * Cc + Jl);
-                    *reinterpret_cast<u32x4_t *>(slab + pl * ROWB + ((ch ^ swz(pl)) << 4)) = v;
-                }
-            }
+        for (int g8 = 0; g8 < KC * 4; ++g8) {
+            const int pl = 8 * g8 + pr;
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (Ii < R && pl < r1 && Jl < Cc) v = *reinterpret_cast<const u32x4_t *>(P + (size_t)pl * plane + (size_t)Ii * Cc + Jl);
+            pre[g8] = v;
         }
-        __syncthreads();
+    };
+    fetch(In, ckn);
+
+    for (long item0 = (long)blockIdx.x * 4; item0 < items; item0 += stride) {
+        const int I = In, J0 = ckn * 64;
+        const bool live = I < R;
+        // The slab is private to the wavefront and a wavefront's LDS operations execute in order: these writes
+        // land after the previous round's fragment reads and before this round's, without a workgroup barrier
+        // (which would also make the wavefront wait for the loads it has just put in flight).
+#pragma unroll
+        for (int g8 = 0; g8 < KC * 4; ++g8) {
+            const int pl = 8 * g8 + pr;
+            *reinterpret_cast<u32x4_t *>(slab + pl * ROWB + ((ch ^ swz(pl)) << 4)) = pre[g8];
+        }
+        In += dI;
+        ckn += dck;
+        if (ckn >= chunks) { ckn -= chunks; ++In; }
+        if (item0 + stride < items) fetch(In, ckn);
         if (!live) continue;
 
         bf16x8_t hf[4];                                     // activation of this lane's tile in product u, entries 4kq..4kq+3
@@ -92,10 +107,10 @@ __global__ __launch_bounds__(256) void recode_mfma_kernel(const bf16_t *__restri
                 v4i16_t t[2];
 #pragma unroll
                 for (int kk = 0; kk < 2; ++kk) {
-                    // source address of this lane inside its 16-lane group: plane 32g + 8kq + 4kk + j/4,
-                    // tiles 16*(j%4) + 4u .. +3 (the group's lane 4c + e receives tile 16c + 4u + e)
+                    // source address of this lane inside its 16-lane group: plane 32g + 8kq + 4kk + j/4, tiles
+                    // 8*(j%4) + 4*(u%2) + 32*(u/2) .. +3 (the group's lane 4c + e receives tile 8c + 4*(u%2) + 32*(u/2) + e)
                     const int row = 32 * g + 8 * kq + 4 * kk + (j >> 2);
-                    const int col = 16 * (j & 3) + 4 * u;
+                    const int col = 8 * (j & 3) + 4 * (u & 1) + 32 * (u >> 1);
                     const char *src = slab + row * ROWB + (((col >> 3) ^ swz(row)) << 4) + ((col & 7) << 1);
                     t[kk] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t *)(
                         (__attribute__((address_space(3))) char *)src));
@@ -108,8 +123,9 @@ __global__ __launch_bounds__(256) void recode_mfma_kernel(const bf16_t *__restri
             hf[u] = __builtin_bit_cast(bf16x8_t, u32x4_t{pack_bf16x2(c0, c1), pack_bf16x2(c2, c3), 0u, 0u});
         }
 
-        // second product: rows = tiles (row 4c + e of product u is tile J0 + 16c + 4u + e), columns = planes
-        const int Jw = J0 + 16 * kq;                        // this lane's 16 tiles
+        // second product: rows = tiles (row 4c + e of product u is tile J0 + 8c + 4*(u%2) + 32*(u/2) + e), columns =
+        // planes; products 2h and 2h+1 leave this lane with the 8 consecutive tiles J0 + 32h + 8kq .. +7
+        const int Jw = J0 + 8 * kq;
 #pragma unroll
         for (int g2 = 0; g2 < 4; ++g2) {
             if (g2 < ng2) {
@@ -124,11 +140,11 @@ __global__ __launch_bounds__(256) void recode_mfma_kernel(const bf16_t *__restri
                     bf16_t *dst = Q + (size_t)pl * plane + (size_t)I * Cc + Jw;
 #pragma unroll
                     for (int half = 0; half < 2; ++half) {
-                        if (Jw + 8 * half < Cc) {
+                        if (Jw + 32 * half < Cc) {
                             const f32x4_t a = o[2 * half], b = o[2 * half + 1];
                             const u32x4_t w = {pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(b[0], b[1]),
                                                pack_bf16x2(b[2], b[3])};
-                            *reinterpret_cast<u32x4_t *>(dst + 8 * half) = w;
+                            *reinterpret_cast<u32x4_t *>(dst + 32 * half) = w;
                         }
                     }
                 }

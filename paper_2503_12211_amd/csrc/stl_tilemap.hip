@@ -150,7 +150,7 @@ __global__ __launch_bounds__(256) void outer_final_kernel(const float *__restric
 __global__ __launch_bounds__(256) void encode_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ E,
                                                           bf16_t *__restrict__ P, int R, int Cc, int r, int chunks)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long item = (long)blockIdx.x * 4 + wave;          // (tile row, chunk of 128 tile columns)
     if (item >= (long)R * chunks) return;
     const int I = (int)(item / chunks), J0 = (int)(item % chunks) * 128;
@@ -316,7 +316,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
     f32x4_t oacc[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) oacc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     char *slab = slab_all[wave];
     const int j = lane & 15, kq = lane >> 4;
 
@@ -343,10 +343,14 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
     const size_t plane = (size_t)R * Cc;
     const size_t ld = (size_t)Cc * 4;
     const long items = (long)R * chunks;
-    for (long item0 = (long)blockIdx.x * 4; item0 < items; item0 += (long)gridDim.x * 4) {
-        const long item = item0 + wave;
-        const bool live = item < items;
-        const int I = live ? (int)(item / chunks) : 0, J0 = live ? (int)(item % chunks) * 64 : 0;
+    // (tile row, chunk) of this wavefront's item, advanced without a division per round
+    const long stride = (long)gridDim.x * 4;
+    int I = (int)(((long)blockIdx.x * 4 + wave) / chunks), ck = (int)(((long)blockIdx.x * 4 + wave) % chunks);
+    const int dI = (int)(stride / chunks), dck = (int)(stride % chunks);
+    for (long item0 = (long)blockIdx.x * 4; item0 < items; item0 += stride, I += dI, ck += dck) {
+        if (ck >= chunks) { ck -= chunks; ++I; }
+        const bool live = I < R;
+        const int J0 = ck * 64;
         __syncthreads();                                    // previous round's fragment reads are done
         if (live) {
             // lane -> (plane within group of 8, 16-byte chunk = 8 tiles)

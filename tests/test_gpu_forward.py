@@ -104,6 +104,23 @@ def test_gelu_epilogue(gu, dtype):
     assert gu.rel(C, ref) <= gu.TOL[dtype]
 
 
+def test_gelu_entrywise_accuracy_fp32(gu):
+    """The device GELU entry by entry: with r = 16 and D the identity the decode of planes holding a grid of
+    values h is gelu(h) itself.  fp32 storage; the bar covers the whole range, tails included."""
+    import torch
+    import paper_2503_12211_amd as stl
+    h = np.linspace(-9.0, 9.0, 16 * 8 * 8).astype(np.float32).reshape(16, 8, 8)
+    prob = stl.Problem(32, 32, 32, 16, stl.STL_F32)
+    Yhat, D = gu.dev(h, "f32"), gu.dev(np.eye(16, dtype=np.float32), "f32")
+    C = torch.empty((32, 32), dtype=torch.float32, device="cuda")
+    stl.stl_decode(prob, Yhat, D, C, stl.STL_FLAG_GELU)
+    torch.cuda.synchronize()
+    got = planes.tiles(gu.host(C)).transpose(2, 0, 1)              # back to (entry = plane, I, J)
+    want = planes.gelu(h.astype(np.float64))
+    assert np.abs(got - want).max() <= 2e-7 * 9.0
+    assert np.all(np.abs(got - want) <= 2e-7 * np.maximum(np.abs(h), 1.0))
+
+
 def test_exact_bases_bf16_inputs(gu):
     """bf16 storage, trivial r=64 basis, small-integer inputs: every intermediate is exactly
     representable, so the result must equal X.W exactly."""

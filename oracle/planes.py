@@ -76,6 +76,19 @@ def backward(X, What, E_X, D, dC, t: int = 4):
     return dX, dWhat, dE_X, dD
 
 
+def encode_weight_backward(W, E_W, dWhat, t: int = 4):
+    """Gradients through the weight encoding What[p,L,J] = sum_q E_W[p,q] w[L,J,q] (the "true encoding" of the
+    paper's plane definition, as opposed to training What directly): with dWhat the gradient of the loss w.r.t.
+    the encoded planes,
+        dw[L,J,q]  = sum_p E_W[p,q] dWhat[p,L,J]          (a decode of dWhat with E_W as decoder)  -> dW (k x n)
+        dE_W[p,q]  = sum_{L,J} dWhat[p,L,J] w[L,J,q].
+    The paper only states that these gradients exist (Section "Strassen-Tile Operator"); this is the chain rule."""
+    dWhat = np.asarray(dWhat, dtype=np.float64)
+    dW = decode(dWhat, E_W, t)
+    dE_W = np.tensordot(dWhat, tiles(W, t), axes=([1, 2], [0, 1]))
+    return dW, dE_W
+
+
 def gelu(h):
     """Exact (erf) GELU, used between the two layers of the MLP-shaped pair."""
     h = np.asarray(h, dtype=np.float64)

@@ -265,6 +265,38 @@ def test_gradients_at_exact_basis_are_textbook():
     assert abs(lhs - rhs) < 1e-11 * abs(rhs)
 
 
+def test_weight_encoding_gradients():
+    """dW and dE_W through What = encode(W, E_W): adjoint identities with random directions, entrywise finite
+    differences of the whole loss <dC, X <> W> (exact: the loss is linear in W and in E_W), and the textbook
+    dW = X^T dC at the exact basis."""
+    m, k, n, r = 8, 12, 16, 11
+    X = RNG.standard_normal((m, k))
+    W = RNG.standard_normal((k, n))
+    E_X, E_W, D = (RNG.standard_normal((r, 16)) * 0.5 for _ in range(3))
+    dC = RNG.standard_normal((m, n))
+    loss = lambda W_, E_: float(np.sum(dC * oracle.forward(X, oracle.encode_weight(W_, E_), E_X, D)))
+    _, dWhat, _, _ = oracle.backward(X, oracle.encode_weight(W, E_W), E_X, D, dC)
+    dW, dE_W = planes.encode_weight_backward(W, E_W, dWhat)
+    assert dW.shape == W.shape and dE_W.shape == E_W.shape
+    V, F = RNG.standard_normal(W.shape), RNG.standard_normal(E_W.shape)
+    assert abs(np.sum(dWhat * oracle.encode_weight(V, E_W)) - np.sum(dW * V)) < 1e-11 * abs(np.sum(dW * V))
+    assert abs(np.sum(dWhat * oracle.encode_weight(W, F)) - np.sum(dE_W * F)) < 1e-11 * abs(np.sum(dE_W * F))
+    base = loss(W, E_W)
+    for (a, b) in [(0, 0), (3, 7), (11, 15), (5, 2)]:
+        Wp = W.copy()
+        Wp[a, b] += 0.5
+        assert abs((loss(Wp, E_W) - base) / 0.5 - dW[a, b]) < 1e-10 * max(1.0, abs(dW[a, b]))
+    for (p_, q) in [(0, 0), (4, 9), (10, 15)]:
+        Ep = E_W.copy()
+        Ep[p_, q] += 0.5
+        assert abs((loss(W, Ep) - base) / 0.5 - dE_W[p_, q]) < 1e-10 * max(1.0, abs(dE_W[p_, q]))
+    # exact basis: the operator is X @ W, so dW must be X^T dC
+    E_X, E_W, D = bases.strassen_4x4()
+    _, dWhat, _, _ = oracle.backward(X, oracle.encode_weight(W, E_W), E_X, D, dC)
+    dW, _ = planes.encode_weight_backward(W, E_W, dWhat)
+    assert rel(dW, X.T @ dC) < 1e-12
+
+
 # --------------------------------------------------------------- inter-layer identity
 def test_algorithm2_fused_decode_encode_identity():
     """Algorithm 2: encoding a decoded output equals one r x r map per tile, Yhat (D E_X^T)."""

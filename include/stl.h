@@ -60,7 +60,7 @@ typedef struct {
 } stl_problem_t;
 
 /* which operation a workspace is sized for */
-enum { STL_OP_ENCODE_WEIGHT = 0, STL_OP_FORWARD = 1, STL_OP_BACKWARD = 2 };
+enum { STL_OP_ENCODE_WEIGHT = 0, STL_OP_FORWARD = 1, STL_OP_BACKWARD = 2, STL_OP_ENCODE_WEIGHT_BACKWARD = 3 };
 
 /* forward variants (low byte of `flags`) and modifiers */
 enum {
@@ -82,6 +82,19 @@ size_t stl_workspace_bytes(const stl_problem_t *prob, int op, int flags);
  */
 stl_status_t stl_encode_weight(const stl_problem_t *prob, const void *W, const void *E_W,
                                void *What, void *stream);
+
+/*
+ * Gradients through the W-encoding, for training W and E_W themselves instead of the encoded planes
+ * (Section "Strassen-Tile Operator": gradients are taken with respect to E_X, E_W, D and W):
+ *   dw[L][J][q] = sum_p E_W[p][q] dWhat[p][L][J]   -> dW,      dE_W[p][q] = sum_{L,J} dWhat[p][L][J] w[L][J][q].
+ * W: k x n, E_W: r x 16 (in).  dWhat: r x K x N fp32 (in), as written by stl_backward.
+ * dW: k x n (out, storage dtype) or NULL.  dE_W: r x 16 fp32 (out) or NULL; accumulate as in stl_backward
+ * (applies to dE_W).  For BF16 storage dWhat is rounded to bf16 once before both sums.
+ * ws / ws_bytes: at least stl_workspace_bytes(prob, STL_OP_ENCODE_WEIGHT_BACKWARD, 0).
+ */
+stl_status_t stl_encode_weight_backward(const stl_problem_t *prob, const void *W, const void *E_W,
+                                        const float *dWhat, void *dW, float *dE_W, int accumulate,
+                                        void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Forward C = X <> W (Definition 3.1 / Eq. (2); Algorithm 1).

@@ -13,13 +13,13 @@ _HERE = Path(__file__).resolve().parent
 _LIB_PATH = _HERE / "libstl_mi355x.so"
 
 STL_F32, STL_BF16 = 0, 1
-STL_OP_ENCODE_WEIGHT, STL_OP_FORWARD, STL_OP_BACKWARD = 0, 1, 2
+STL_OP_ENCODE_WEIGHT, STL_OP_FORWARD, STL_OP_BACKWARD, STL_OP_ENCODE_WEIGHT_BACKWARD = 0, 1, 2, 3
 STL_FLAG_AUTO, STL_FLAG_UNFUSED, STL_FLAG_EPILOGUE, STL_FLAG_FUSED = 0, 1, 2, 3
 STL_FLAG_GELU = 0x100
 
 # every symbol include/stl.h declares
 SYMBOLS = (
-    "stl_workspace_bytes", "stl_encode_weight", "stl_forward", "stl_backward", "stl_encode_activation",
+    "stl_workspace_bytes", "stl_encode_weight", "stl_encode_weight_backward", "stl_forward", "stl_backward", "stl_encode_activation",
     "stl_plane_matmul", "stl_decode", "stl_mlp_workspace_bytes", "stl_mlp_forward", "stl_recode",
     "stl_status_string", "stl_last_error", "stl_version",
 )
@@ -69,6 +69,7 @@ def _load():
     lib.stl_workspace_bytes.restype = ctypes.c_size_t
     lib.stl_workspace_bytes.argtypes = [pp, ctypes.c_int, ctypes.c_int]
     lib.stl_encode_weight.argtypes = [pp, _P, _P, _P, _P]
+    lib.stl_encode_weight_backward.argtypes = [pp, _P, _P, _P, _P, _P, ctypes.c_int, _P, ctypes.c_size_t, _P]
     lib.stl_forward.argtypes = [pp, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, ctypes.c_int, _P]
     lib.stl_backward.argtypes = [pp, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_int, _P, ctypes.c_size_t, _P]
     lib.stl_encode_activation.argtypes = [pp, _P, _P, _P, _P]
@@ -79,7 +80,7 @@ def _load():
     lib.stl_mlp_forward.argtypes = [pp, pp, _P, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, ctypes.c_int, _P]
     lib.stl_recode.argtypes = [pp, pp, _P, _P, _P, _P, _P, ctypes.c_int, _P]
     for name in ("stl_encode_weight", "stl_forward", "stl_backward", "stl_encode_activation", "stl_plane_matmul",
-                 "stl_decode", "stl_mlp_forward", "stl_recode"):
+                 "stl_decode", "stl_mlp_forward", "stl_recode", "stl_encode_weight_backward"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stl_status_string.restype = ctypes.c_char_p
     lib.stl_status_string.argtypes = [ctypes.c_int]
@@ -135,6 +136,12 @@ def stl_workspace_bytes(prob: Problem, op: int, flags: int = 0) -> int:
 
 def stl_encode_weight(prob: Problem, W, E_W, What, stream=None) -> None:
     _check(_load().stl_encode_weight(ctypes.byref(prob.c()), _ptr(W), _ptr(E_W), _ptr(What), _stream(stream)))
+
+
+def stl_encode_weight_backward(prob: Problem, W, E_W, dWhat, dW, dE_W, accumulate: int = 0, ws=None, ws_bytes: int = 0,
+                               stream=None) -> None:
+    _check(_load().stl_encode_weight_backward(ctypes.byref(prob.c()), _ptr(W), _ptr(E_W), _ptr(dWhat), _ptr(dW), _ptr(dE_W),
+                                              accumulate, _ptr(ws), ws_bytes, _stream(stream)))
 
 
 def stl_forward(prob: Problem, X, What, E_X, D, C, Xhat_save=None, Yhat_save=None, ws=None, ws_bytes: int = 0,

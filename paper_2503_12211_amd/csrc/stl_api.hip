@@ -112,6 +112,26 @@ BwdWs bwd_layout(const Dims &d)
     return w;
 }
 
+struct EwbWs {
+    size_t planes, part, total;
+};
+
+// backward of the weight encoding: a bf16 copy of dWhat (bf16 storage only) and the partial sums of dE_W
+EwbWs ewb_layout(const stl_problem_t *p, const Dims &d)
+{
+    EwbWs w{};
+    size_t off = 0;
+    w.planes = off;
+    if (p->dtype == STL_BF16) off += align256((size_t)d.r * d.K * d.N * 2);
+    int nb = stl::outer_reduce_blocks((int64_t)d.K * d.N);
+    const int nb_f = stl::decode_outer_blocks(d.K, d.N);
+    nb = nb > nb_f ? nb : nb_f;
+    w.part = off;
+    off += align256((size_t)nb * d.r * 16 * sizeof(float));
+    w.total = off;
+    return w;
+}
+
 struct MlpWs {
     size_t xhat1, yhat1, xhat2, yhat2, hidden, total;
     bool one_pass;
@@ -199,6 +219,7 @@ size_t stl_workspace_bytes(const stl_problem_t *prob, int op, int flags)
             return fwd_layout(d, v).total;
         }
         case STL_OP_BACKWARD: return bwd_layout(d).total;
+        case STL_OP_ENCODE_WEIGHT_BACKWARD: return ewb_layout(prob, d).total;
     }
     fail(STL_ERR_INVALID_ARG, "unknown op %d", op);
     return 0;
@@ -211,6 +232,40 @@ stl_status_t stl_encode_weight(const stl_problem_t *prob, const void *W, const v
     if (st != STL_OK) return st;
     if (!W || !E_W || !What) return fail(STL_ERR_INVALID_ARG, "stl_encode_weight: NULL pointer");
     STL_HIP(stl::launch_encode(prob->dtype, W, E_W, What, d.K, d.N, d.r, (hipStream_t)stream), "encode_weight");
+    return STL_OK;
+}
+
+stl_status_t stl_encode_weight_backward(const stl_problem_t *prob, const void *W, const void *E_W, const float *dWhat,
+                                        void *dW, float *dE_W, int accumulate, void *ws, size_t ws_bytes, void *stream)
+{
+    Dims d;
+    stl_status_t st = check_problem(prob, &d);
+    if (st != STL_OK) return st;
+    if (!W || !E_W || !dWhat) return fail(STL_ERR_INVALID_ARG, "stl_encode_weight_backward: NULL input pointer");
+    if (accumulate != 0 && accumulate != 1)
+        return fail(STL_ERR_INVALID_ARG, "stl_encode_weight_backward: accumulate must be 0 or 1");
+    const EwbWs w = ewb_layout(prob, d);
+    if (!ws || ws_bytes < w.total)
+        return fail(STL_ERR_WORKSPACE, "stl_encode_weight_backward: workspace of %zu bytes needed, %zu given", w.total,
+                    ws ? ws_bytes : 0);
+    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_encode_weight_backward: workspace is not 16-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    const int dt = prob->dtype;
+    char *base = (char *)ws;
+    float *part = (float *)(base + w.part);
+    const void *planes = dWhat;
+    if (dt == STL_BF16 && (dW || dE_W)) {
+        STL_HIP(stl::launch_cast_bf16(dWhat, base + w.planes, (size_t)d.r * d.K * d.N, s), "encode_weight_backward/round dWhat");
+        planes = base + w.planes;
+    }
+    if (dW && dE_W && stl::decode_outer_eligible(dt, d.N)) {
+        STL_HIP(stl::launch_decode_outer(planes, E_W, dW, W, dE_W, part, d.K, d.N, d.r, accumulate, s),
+                "encode_weight_backward/dW + dE_W");
+        return STL_OK;
+    }
+    if (dW) STL_HIP(stl::launch_decode(dt, planes, E_W, dW, d.K, d.N, d.r, false, s), "encode_weight_backward/dW");
+    if (dE_W)
+        STL_HIP(stl::launch_outer_reduce(dt, planes, W, dE_W, part, d.K, d.N, d.r, accumulate, s), "encode_weight_backward/dE_W");
     return STL_OK;
 }
 

@@ -25,6 +25,9 @@ int decode_outer_blocks(int R, int Cc);
 hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const void *V, float *G, float *part, int R,
                                int Cc, int r, int accumulate, hipStream_t s);
 
+// out[i] = bf16(in[i]), round to nearest even
+hipError_t launch_cast_bf16(const float *in, void *out, size_t n, hipStream_t s);
+
 // inter-layer step of two stacked layers in one pass (bf16): Q[s] <- encode_{E2}( act( decode_{Dm}(P) ) ), planes P
 // r1 x R x Cc -> planes Q r2 x R x Cc, the hidden activation never stored
 bool recode_eligible(int dtype, int Cc);

@@ -439,9 +439,30 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
     }
 }
 
+// fp32 -> bf16 (round to nearest even), 8 elements per thread; n8 = number of 8-element groups, tail handled per element
+__global__ __launch_bounds__(256) void cast_bf16_kernel(const float *__restrict__ in, bf16_t *__restrict__ out, size_t n)
+{
+    const size_t n8 = n / 8;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+        const f32x4_t a = reinterpret_cast<const f32x4_t *>(in)[2 * i], b = reinterpret_cast<const f32x4_t *>(in)[2 * i + 1];
+        reinterpret_cast<u32x4_t *>(out)[i] = u32x4_t{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(b[0], b[1]),
+                                                      pack_bf16x2(b[2], b[3])};
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 7)) out[n8 * 8 + threadIdx.x] = f32_to_bf16(in[n8 * 8 + threadIdx.x]);
+}
+
 // ---------------------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------------------
+hipError_t launch_cast_bf16(const float *in, void *out, size_t n, hipStream_t s)
+{
+    size_t blocks = (n / 8 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, in, (bf16_t *)out, n);
+    return hipGetLastError();
+}
+
 template <typename T>
 static hipError_t launch_encode_t(const void *A, const void *E, void *P, int R, int Cc, int r, hipStream_t s)
 {

@@ -102,3 +102,20 @@ def recode(Yhat1, D1, E2, dtype, flags=0, with_scratch=False):
     stl.stl_recode(up, down, Y, D, E, Xh2, H, flags)
     torch.cuda.synchronize()
     return host(Xh2)
+
+
+def encode_weight_backward(W, E_W, dWhat, dtype, accumulate=0, init=None, skip=()):
+    """W (k, n), E_W (r, 16), dWhat (r, K, N) fp32 -> dict(dW, dE_W) as float64 numpy."""
+    k, n = W.shape
+    r = E_W.shape[0]
+    prob = stl.Problem(4, k, n, r, STL_DT[dtype])                 # m plays no part in the weight encoding
+    Wd, Ed = dev(W, dtype), dev(E_W, dtype)
+    dWh = torch.from_numpy(np.ascontiguousarray(dWhat, dtype=np.float32)).cuda()
+    dW = torch.full((k, n), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
+    dE = (torch.full((r, 16), float("nan"), dtype=torch.float32, device="cuda") if init is None
+          else torch.from_numpy(np.asarray(init, dtype=np.float32)).cuda())
+    ws, nbytes = workspace(prob, stl.STL_OP_ENCODE_WEIGHT_BACKWARD)
+    stl.stl_encode_weight_backward(prob, Wd, Ed, dWh, None if "dW" in skip else dW, None if "dE_W" in skip else dE,
+                                   accumulate, ws, nbytes)
+    torch.cuda.synchronize()
+    return {"dW": host(dW), "dE_W": host(dE)}

@@ -127,3 +127,17 @@ def test_layer_pair_argument_checks():
     with pytest.raises(stl.StlError) as e:
         stl.stl_recode(up32, down32, FAKE, FAKE, FAKE, FAKE, None, 0, stream=0)
     assert e.value.status == 1
+
+
+def test_weight_encoding_backward_argument_checks():
+    prob = stl.Problem(256, 256, 512, 32, stl.STL_BF16)
+    need = stl.stl_workspace_bytes(prob, stl.STL_OP_ENCODE_WEIGHT_BACKWARD)
+    assert need >= 2 * 32 * 64 * 128                       # holds a bf16 copy of the planes
+    need32 = stl.stl_workspace_bytes(stl.Problem(256, 256, 512, 32, stl.STL_F32), stl.STL_OP_ENCODE_WEIGHT_BACKWARD)
+    assert 0 < need32 < need                               # fp32 storage: partial sums only
+    for args, status in (((None, FAKE, FAKE, FAKE, FAKE, 0, FAKE, 1 << 40), 1), ((FAKE, FAKE, None, FAKE, FAKE, 0, FAKE, 1 << 40), 1),
+                         ((FAKE, FAKE, FAKE, FAKE, FAKE, 2, FAKE, 1 << 40), 1), ((FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, need - 1), 3),
+                         ((FAKE, FAKE, FAKE, FAKE, FAKE, 0, None, 0), 3)):
+        with pytest.raises(stl.StlError) as e:
+            stl.stl_encode_weight_backward(prob, *args, stream=0)
+        assert e.value.status == status

@@ -104,8 +104,10 @@ BwdWs bwd_layout(const Dims &d)
     off += pn;
     int nb = stl::outer_reduce_blocks((int64_t)d.M * d.N);
     const int nb_k = stl::outer_reduce_blocks((int64_t)d.M * d.K), nb_f = stl::decode_outer_blocks(d.M, d.K);
+    const int nb_e = stl::encode_outer_blocks(d.M, d.N);
     nb = nb > nb_k ? nb : nb_k;
     nb = nb > nb_f ? nb : nb_f;
+    nb = nb > nb_e ? nb : nb_e;
     w.part = off;
     off += align256((size_t)nb * d.r * 16 * sizeof(float));
     w.total = off;
@@ -369,15 +371,18 @@ stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *
     const bool need_xhat = dWhat || (dD && !Yhat_saved);
     if (need_xhat && !Xhat_saved)
         STL_HIP(stl::launch_encode(dt, X, E_X, base + w.xhat, d.M, d.K, d.r, s), "backward/encode X");
-    STL_HIP(stl::launch_encode(dt, dC, D, dyhat, d.M, d.N, d.r, s), "backward/encode dC");
-    if (dD) {
-        const void *yhat = Yhat_saved;
-        if (!yhat) {
-            stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false};
-            STL_HIP(stl::launch_plane_gemm(dt, g, xhat, What, base + w.yhat, s), "backward/recompute Yhat");
-            yhat = base + w.yhat;
-        }
-        STL_HIP(stl::launch_outer_reduce(dt, yhat, dC, dD, part, d.M, d.N, d.r, accumulate, s), "backward/dD");
+    const void *yhat = Yhat_saved;
+    if (dD && !yhat) {
+        stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false};
+        STL_HIP(stl::launch_plane_gemm(dt, g, xhat, What, base + w.yhat, s), "backward/recompute Yhat");
+        yhat = base + w.yhat;
+    }
+    if (dD && stl::encode_outer_eligible(dt, d.N)) {
+        // one pass over dC: dYhat = encode with D, dD = sum over tiles of Yhat (x) dc
+        STL_HIP(stl::launch_encode_outer(dC, D, dyhat, yhat, dD, part, d.M, d.N, d.r, accumulate, s), "backward/dYhat + dD");
+    } else {
+        STL_HIP(stl::launch_encode(dt, dC, D, dyhat, d.M, d.N, d.r, s), "backward/encode dC");
+        if (dD) STL_HIP(stl::launch_outer_reduce(dt, yhat, dC, dD, part, d.M, d.N, d.r, accumulate, s), "backward/dD");
     }
     if (dX || dE_X) {
         // dXhat[p] = dYhat[p] * What[p]^T : contraction over J, What[p] is stored [L][J]

@@ -25,6 +25,16 @@ int decode_outer_blocks(int R, int Cc);
 hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const void *V, float *G, float *part, int R,
                                int Cc, int r, int accumulate, hipStream_t s);
 
+// G[i] (+)= sum over nb partials part[b][i], i < n_out, in block order (second stage of the basis-gradient sums)
+hipError_t launch_outer_final(const float *part, float *G, int nb, int n_out, int accumulate, hipStream_t s);
+
+// encode and basis gradient in one pass over the matrix (bf16): P <- encode(A, E), G (+)= Qp . tileview(A);
+// `part` holds encode_outer_blocks(R, Cc) * r * 16 floats
+bool encode_outer_eligible(int dtype, int Cc);
+int encode_outer_blocks(int R, int Cc);
+hipError_t launch_encode_outer(const void *A, const void *E, void *P, const void *Qp, float *G, float *part, int R, int Cc,
+                               int r, int accumulate, hipStream_t s);
+
 // out[i] = bf16(in[i]), round to nearest even
 hipError_t launch_cast_bf16(const float *in, void *out, size_t n, hipStream_t s);
 

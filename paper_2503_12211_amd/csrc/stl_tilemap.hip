@@ -268,7 +268,8 @@ __global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restric
         for (int s = 0; s < 2; ++s)
 #pragma unroll
             for (int g = 0; g < 4; ++g) pc[s][g] = pa[s][g];
-        __syncthreads();
+        // sV[wave] is private to the wavefront and a wavefront's LDS operations execute in order: no workgroup barrier
+        // (a barrier would also make the wavefront wait for the loads it is about to put in flight)
         if (base + 256 < t1) fetch(base + 256);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
@@ -278,7 +279,6 @@ __global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restric
                 if (g < ngroups)
                     acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, pc[s][g]), fb, acc[g], 0, 0, 0);
         }
-        __syncthreads();
     }
     // accumulator element e of group g: plane 16g + 4*(lane/16) + e, tile entry lane%16
 #pragma unroll
@@ -351,7 +351,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
         if (ck >= chunks) { ck -= chunks; ++I; }
         const bool live = I < R;
         const int J0 = ck * 64;
-        __syncthreads();                                    // previous round's fragment reads are done
+        // slab and sV belong to this wavefront alone and its LDS operations execute in order: the writes below land
+        // after the previous round's fragment reads without a workgroup barrier
         if (live) {
             // lane -> (plane within group of 8, 16-byte chunk = 8 tiles)
             const int pr = lane >> 3, ch = lane & 7;
@@ -378,7 +379,6 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
                 }
             }
         }
-        __syncthreads();
         if (live && OUTER) {
             // K = 32 tiles per MFMA: A = planes x tiles from the slab (lane: plane 16g + j, tiles 32s + 8kq ..),
             // B = tiles x entries from sV (lane: entry j, same tiles)
@@ -517,6 +517,12 @@ hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, i
     }
     return dtype == 0 ? launch_decode_t<float>(P, Dm, Cmat, R, Cc, r, gelu, s)
                       : launch_decode_t<bf16_t>(P, Dm, Cmat, R, Cc, r, gelu, s);
+}
+
+hipError_t launch_outer_final(const float *part, float *G, int nb, int n_out, int accumulate, hipStream_t s)
+{
+    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 15) / 16), dim3(256), 0, s, part, G, nb, n_out, accumulate);
+    return hipGetLastError();
 }
 
 bool decode_outer_eligible(int dtype, int Cc) { return dtype == 1 && (Cc % 8) == 0; }

@@ -35,6 +35,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C5", help="C5 (default), C2, or m,k,n,r")
     ap.add_argument("--sweep", action="store_true", help="also time the forward r sweep (m=8192,k=n=4096)")
+    ap.add_argument("--sweep-big", action="store_true", help="with --sweep: include n=16384 in the square sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mlp", action="store_true", help="skip the stacked-layer (MLP-shaped pair) leg")
     ap.add_argument("--profile-only", default="",
@@ -330,6 +331,31 @@ def main():
         C2 = torch.empty((8192, 4096), dtype=bf, device="cuda")
         sweep["dense"] = round(T.wall(lambda: torch.matmul(X2, Wd2, out=C2), S, W), 5)
         out["forward_r_sweep_ms_m8192_k4096_n4096"] = sweep
+        del Wd2, X2, C2
+        # the paper's own timing workload: square n x n matrices, forward only (its speed-up figure); 16384 is left
+        # to --sweep-big (3 GB of planes at r = 49)
+        sq = {}
+        for nn in (4096, 8192) + ((16384,) if args.sweep_big else ()):
+            Xq = torch.randn((nn, nn), device="cuda").to(bf)
+            Wq = (torch.randn((nn, nn), device="cuda") * nn ** -0.5).to(bf)
+            Cq = torch.empty((nn, nn), dtype=bf, device="cuda")
+            row = {"dense": round(T.wall(lambda: torch.matmul(Xq, Wq, out=Cq), max(S // 4, 3), 3), 5)}
+            del Wq
+            for rr in (16, 24, 32, 49):
+                pr = stl.Problem(nn, nn, nn, rr, stl.STL_BF16)
+                Whq = (torch.randn((rr, nn // 4, nn // 4), device="cuda") * nn ** -0.5).to(bf)
+                Eq = (torch.randn((rr, 16), device="cuda") * 0.25).to(bf)
+                Dq = (torch.randn((rr, 16), device="cuda") * 0.25).to(bf)
+                nbq = stl.stl_workspace_bytes(pr, stl.STL_OP_FORWARD, 0)
+                wsq = torch.empty(nbq, dtype=torch.uint8, device="cuda")
+                row[str(rr)] = round(T.wall(lambda: stl.stl_forward(pr, Xq, Whq, Eq, Dq, Cq, None, None, wsq, nbq, 0),
+                                            max(S // 4, 3), 3), 5)
+                del Whq, wsq
+            row["speedup_r32"] = round(row["dense"] / row["32"], 3)
+            sq[str(nn)] = row
+            log(f"  square n={nn}: {row}")
+            del Xq, Cq
+        out["forward_square_ms"] = sq
 
     if not args.no_cpu_baseline:
         import oracle

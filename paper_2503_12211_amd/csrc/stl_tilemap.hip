@@ -333,9 +333,6 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
         }
         fa[g] = __builtin_bit_cast(bf16x8_t, u32x4_t{w[0], w[1], w[2], w[3]});
     }
-    // rows of planes >= r are never loaded: keep them zero (they meet zero A entries, but must be finite)
-    for (int i = lane; i < KC * 32 * ROWB / 16; i += 64) reinterpret_cast<u32x4_t *>(slab)[i] = u32x4_t{0u, 0u, 0u, 0u};
-
     // swizzle of the 16-byte chunk index inside a row, so that the 8 plane rows one transposing read touches
     // (planes 0-3 and 8-11, or 4-7 and 12-15, of a 16-tile column group) fall into different bank windows
     auto swz = [](int row) { return ((((row >> 1) & 1) | (((row >> 3) & 1) << 1)) << 1); };
@@ -345,40 +342,62 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
     const long items = (long)R * chunks;
     // (tile row, chunk) of this wavefront's item, advanced without a division per round
     const long stride = (long)gridDim.x * 4;
-    int I = (int)(((long)blockIdx.x * 4 + wave) / chunks), ck = (int)(((long)blockIdx.x * 4 + wave) % chunks);
+    int In = (int)(((long)blockIdx.x * 4 + wave) / chunks), ckn = (int)(((long)blockIdx.x * 4 + wave) % chunks);
     const int dI = (int)(stride / chunks), dck = (int)(stride % chunks);
-    for (long item0 = (long)blockIdx.x * 4; item0 < items; item0 += stride, I += dI, ck += dck) {
-        if (ck >= chunks) { ck -= chunks; ++I; }
-        const bool live = I < R;
-        const int J0 = ck * 64;
-        // slab and sV belong to this wavefront alone and its LDS operations execute in order: the writes below land
-        // after the previous round's fragment reads without a workgroup barrier
-        if (live) {
-            // lane -> (plane within group of 8, 16-byte chunk = 8 tiles)
-            const int pr = lane >> 3, ch = lane & 7;
-            const int Jl = J0 + 8 * ch;
+
+    // Loader role of a lane: plane 8*g8 + pr, 16-byte chunk ch (8 tiles) -- whole 128-byte lines, 8 planes per
+    // instruction; with OUTER also tile J0 + lane of V (4 rows x 8 bytes).  The NEXT item's operands are fetched into
+    // registers while the current item is computed and stored.
+    const int pr = lane >> 3, ch = lane & 7;
+    u32x4_t pre[KC * 4];
+    u32x2_t xpre[OUTER ? 4 : 1];
+    auto fetch = [&](int Ii, int cki) {
+        const int Jl = cki * 64 + 8 * ch;
 #pragma unroll
-            for (int g8 = 0; g8 < KC * 4; ++g8) {
-                const int pl = 8 * g8 + pr;
-                if (pl < r && Jl < Cc) {
-                    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(P + (size_t)pl * plane + (size_t)I * Cc + Jl);
-                    *reinterpret_cast<u32x4_t *>(slab + pl * ROWB + ((ch ^ swz(pl)) << 4)) = v;
-                }
-            }
-            if (OUTER) {
-                // lane = tile J0 + lane: its 16 entries (4 rows x 8 bytes) -> sV[entry][tile]
-                const int Jt = J0 + lane;
+        for (int g8 = 0; g8 < KC * 4; ++g8) {
+            const int pl = 8 * g8 + pr;
+            u32x4_t v = {0u, 0u, 0u, 0u};       // planes >= r stay zero (they meet zero D entries, but must be finite)
+            if (Ii < R && pl < r && Jl < Cc) v = *reinterpret_cast<const u32x4_t *>(P + (size_t)pl * plane + (size_t)Ii * Cc + Jl);
+            pre[g8] = v;
+        }
+        if (OUTER) {
+            const int Jt = cki * 64 + lane;
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    u32x2_t xv = {0u, 0u};
-                    if (Jt < Cc) xv = *reinterpret_cast<const u32x2_t *>(V + ((size_t)I * 4 + a) * ld + (size_t)Jt * 4);
-                    sV[wave][4 * a + 0][lane] = (bf16_t)(xv[0] & 0xffffu);
-                    sV[wave][4 * a + 1][lane] = (bf16_t)(xv[0] >> 16);
-                    sV[wave][4 * a + 2][lane] = (bf16_t)(xv[1] & 0xffffu);
-                    sV[wave][4 * a + 3][lane] = (bf16_t)(xv[1] >> 16);
-                }
+            for (int a = 0; a < 4; ++a) {
+                u32x2_t xv = {0u, 0u};
+                if (Ii < R && Jt < Cc) xv = *reinterpret_cast<const u32x2_t *>(V + ((size_t)Ii * 4 + a) * ld + (size_t)Jt * 4);
+                xpre[a] = xv;
             }
         }
+    };
+    fetch(In, ckn);
+
+    for (long item0 = (long)blockIdx.x * 4; item0 < items; item0 += stride) {
+        const int I = In, J0 = ckn * 64;
+        const bool live = I < R;
+        // slab and sV belong to this wavefront alone and its LDS operations execute in order: the writes below land
+        // after the previous round's fragment reads without a workgroup barrier (which would also make the wavefront
+        // wait for the loads it is about to put in flight)
+#pragma unroll
+        for (int g8 = 0; g8 < KC * 4; ++g8) {
+            const int pl = 8 * g8 + pr;
+            *reinterpret_cast<u32x4_t *>(slab + pl * ROWB + ((ch ^ swz(pl)) << 4)) = pre[g8];
+        }
+        if (OUTER) {
+            // lane = tile J0 + lane: its 16 entries (4 rows x 8 bytes) -> sV[entry][tile]
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const u32x2_t xv = xpre[a];
+                sV[wave][4 * a + 0][lane] = (bf16_t)(xv[0] & 0xffffu);
+                sV[wave][4 * a + 1][lane] = (bf16_t)(xv[0] >> 16);
+                sV[wave][4 * a + 2][lane] = (bf16_t)(xv[1] & 0xffffu);
+                sV[wave][4 * a + 3][lane] = (bf16_t)(xv[1] >> 16);
+            }
+        }
+        In += dI;
+        ckn += dck;
+        if (ckn >= chunks) { ckn -= chunks; ++In; }
+        if (item0 + stride < items) fetch(In, ckn);
         if (live && OUTER) {
             // K = 32 tiles per MFMA: A = planes x tiles from the slab (lane: plane 16g + j, tiles 32s + 8kq ..),
             // B = tiles x entries from sV (lane: entry j, same tiles)

@@ -1,0 +1,35 @@
+"""The Class-0 fitting example: its own basis generator (CPU) and a short training run through the library (GPU)."""
+import numpy as np
+import pytest
+
+from paper_2503_12211_amd.examples import class0_fit
+
+
+def test_example_basis_is_exact_and_matches_the_oracle_fixture():
+    """The example builds its own r=49 basis (product code shares nothing with the oracle): it must multiply 4x4
+    tiles exactly and equal the oracle's fixture row for row."""
+    from oracle import bases
+    E_X, E_W, D = class0_fit.seven_product_basis_4x4()
+    rng = np.random.default_rng(0)
+    X, W = rng.standard_normal((4, 4)), rng.standard_normal((4, 4))
+    c = D.T @ ((E_X @ X.reshape(-1)) * (E_W @ W.reshape(-1)))
+    assert np.abs(c.reshape(4, 4) - X @ W).max() < 1e-14
+    for mine, ref in zip((E_X, E_W, D), bases.strassen_4x4()):
+        assert np.array_equal(mine, ref)
+
+
+@pytest.mark.gpu
+def test_class0_fit_trains_through_the_library():
+    # exact basis: the residual of the first step is fp32 rounding noise (Adam then moves the bases by about its
+    # step size whatever the gradient's magnitude, so later steps only have to stay small)
+    h = class0_fit.fit(49, steps=3, init="strassen", size=64)
+    assert h[0] < 1e-9 and max(h) < 1e-2, h
+    # pruned basis and Gaussian start: the error estimate must fall (per-entry variance of X W is 4)
+    for init in ("strassen", "gauss"):
+        h = class0_fit.fit(32, steps=120, init=init, size=64, seed=3)
+        assert np.isfinite(h).all()
+        assert np.mean(h[-10:]) < 0.6 * np.mean(h[:3]), (init, h[:3], h[-10:])
+    # and more planes fit better than fewer, from the same kind of start
+    h16 = class0_fit.fit(16, steps=120, init="gauss", size=64, seed=3)
+    h48 = class0_fit.fit(48, steps=120, init="gauss", size=64, seed=3)
+    assert np.mean(h48[-10:]) < np.mean(h16[-10:])

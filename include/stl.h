@@ -17,7 +17,8 @@
  *    row-major: vec(T)[a*t+b] = T[a][b].  E_X, E_W, D are r x t^2 row-major
  *    (Definition 3.1); the decoder is applied as D^T.
  *  - Plane tensors (What, Xhat, Yhat, dWhat) are plane-major: [p][row tile][col tile].
- *  - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned.
+ *  - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned
+ *    (STL_ERR_INVALID_ARG otherwise).
  *    The library allocates and frees no device memory: scratch comes from `ws`
  *    (size from stl_workspace_bytes).  Outputs must not alias inputs or `ws`.
  *  - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL is

@@ -56,6 +56,13 @@ stl_status_t check_problem(const stl_problem_t *p, Dims *d)
     return STL_OK;
 }
 
+// every data pointer must be 16-byte aligned (vector loads and stores of 16 bytes start at row and plane bases)
+template <typename... P>
+bool any_misaligned(P... ptrs)
+{
+    return ((((uintptr_t)ptrs) & 15) || ...);
+}
+
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct FwdWs {
@@ -233,6 +240,7 @@ stl_status_t stl_encode_weight(const stl_problem_t *prob, const void *W, const v
     stl_status_t st = check_problem(prob, &d);
     if (st != STL_OK) return st;
     if (!W || !E_W || !What) return fail(STL_ERR_INVALID_ARG, "stl_encode_weight: NULL pointer");
+    if (any_misaligned(W, E_W, What)) return fail(STL_ERR_INVALID_ARG, "stl_encode_weight: pointer not 16-byte aligned");
     STL_HIP(stl::launch_encode(prob->dtype, W, E_W, What, d.K, d.N, d.r, (hipStream_t)stream), "encode_weight");
     return STL_OK;
 }
@@ -244,6 +252,8 @@ stl_status_t stl_encode_weight_backward(const stl_problem_t *prob, const void *W
     stl_status_t st = check_problem(prob, &d);
     if (st != STL_OK) return st;
     if (!W || !E_W || !dWhat) return fail(STL_ERR_INVALID_ARG, "stl_encode_weight_backward: NULL input pointer");
+    if (any_misaligned(W, E_W, dWhat, dW, dE_W))
+        return fail(STL_ERR_INVALID_ARG, "stl_encode_weight_backward: pointer not 16-byte aligned");
     if (accumulate != 0 && accumulate != 1)
         return fail(STL_ERR_INVALID_ARG, "stl_encode_weight_backward: accumulate must be 0 or 1");
     const EwbWs w = ewb_layout(prob, d);
@@ -277,6 +287,7 @@ stl_status_t stl_encode_activation(const stl_problem_t *prob, const void *X, con
     stl_status_t st = check_problem(prob, &d);
     if (st != STL_OK) return st;
     if (!X || !E_X || !Xhat) return fail(STL_ERR_INVALID_ARG, "stl_encode_activation: NULL pointer");
+    if (any_misaligned(X, E_X, Xhat)) return fail(STL_ERR_INVALID_ARG, "stl_encode_activation: pointer not 16-byte aligned");
     STL_HIP(stl::launch_encode(prob->dtype, X, E_X, Xhat, d.M, d.K, d.r, (hipStream_t)stream), "encode_activation");
     return STL_OK;
 }
@@ -287,6 +298,7 @@ stl_status_t stl_plane_matmul(const stl_problem_t *prob, const void *Xhat, const
     stl_status_t st = check_problem(prob, &d);
     if (st != STL_OK) return st;
     if (!Xhat || !What || !Yhat) return fail(STL_ERR_INVALID_ARG, "stl_plane_matmul: NULL pointer");
+    if (any_misaligned(Xhat, What, Yhat)) return fail(STL_ERR_INVALID_ARG, "stl_plane_matmul: pointer not 16-byte aligned");
     stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false};
     STL_HIP(stl::launch_plane_gemm(prob->dtype, g, Xhat, What, Yhat, (hipStream_t)stream), "plane_matmul");
     return STL_OK;
@@ -298,6 +310,7 @@ stl_status_t stl_decode(const stl_problem_t *prob, const void *Yhat, const void 
     stl_status_t st = check_problem(prob, &d);
     if (st != STL_OK) return st;
     if (!Yhat || !D || !C) return fail(STL_ERR_INVALID_ARG, "stl_decode: NULL pointer");
+    if (any_misaligned(Yhat, D, C)) return fail(STL_ERR_INVALID_ARG, "stl_decode: pointer not 16-byte aligned");
     if (flags & ~STL_FLAG_GELU) return fail(STL_ERR_UNSUPPORTED, "stl_decode: unknown flag bits 0x%x", flags);
     STL_HIP(stl::launch_decode(prob->dtype, Yhat, D, C, d.M, d.N, d.r, (flags & STL_FLAG_GELU) != 0, (hipStream_t)stream),
             "decode");
@@ -314,6 +327,8 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
     st = check_flags(flags, &variant);
     if (st != STL_OK) return st;
     if (!X || !What || !E_X || !D || !C) return fail(STL_ERR_INVALID_ARG, "stl_forward: NULL pointer");
+    if (any_misaligned(X, What, E_X, D, C, Xhat_save, Yhat_save))
+        return fail(STL_ERR_INVALID_ARG, "stl_forward: pointer not 16-byte aligned");
     if (variant == STL_FLAG_EPILOGUE || variant == STL_FLAG_FUSED) {
         if (!stl::block_forward_eligible(prob->dtype, d.M, d.K, d.N, d.r))
             return fail(STL_ERR_UNSUPPORTED,
@@ -356,6 +371,8 @@ stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *
     stl_status_t st = check_problem(prob, &d);
     if (st != STL_OK) return st;
     if (!X || !What || !E_X || !D || !dC) return fail(STL_ERR_INVALID_ARG, "stl_backward: NULL input pointer");
+    if (any_misaligned(X, What, E_X, D, dC, Xhat_saved, Yhat_saved, dX, dWhat, dE_X, dD))
+        return fail(STL_ERR_INVALID_ARG, "stl_backward: pointer not 16-byte aligned");
     if (accumulate != 0 && accumulate != 1) return fail(STL_ERR_INVALID_ARG, "stl_backward: accumulate must be 0 or 1");
     const BwdWs w = bwd_layout(d);
     if (!ws || ws_bytes < w.total)
@@ -423,6 +440,7 @@ stl_status_t stl_recode(const stl_problem_t *up, const stl_problem_t *down, cons
     st = check_pair_flags(flags, &variant);
     if (st != STL_OK) return st;
     if (!Yhat1 || !D1 || !E_X2 || !Xhat2) return fail(STL_ERR_INVALID_ARG, "stl_recode: NULL pointer");
+    if (any_misaligned(Yhat1, D1, E_X2, Xhat2, H)) return fail(STL_ERR_INVALID_ARG, "stl_recode: pointer not 16-byte aligned");
     hipStream_t s = (hipStream_t)stream;
     const bool gelu = (flags & STL_FLAG_GELU) != 0;
     if (variant == STL_FLAG_AUTO && stl::recode_eligible(up->dtype, d1.N)) {
@@ -447,6 +465,8 @@ stl_status_t stl_mlp_forward(const stl_problem_t *up, const stl_problem_t *down,
     if (st != STL_OK) return st;
     if (!X || !What1 || !E_X1 || !D1 || !What2 || !E_X2 || !D2 || !C)
         return fail(STL_ERR_INVALID_ARG, "stl_mlp_forward: NULL pointer");
+    if (any_misaligned(X, What1, E_X1, D1, What2, E_X2, D2, C))
+        return fail(STL_ERR_INVALID_ARG, "stl_mlp_forward: pointer not 16-byte aligned");
     const MlpWs w = mlp_layout(up, d1, d2, variant);
     if (!ws || ws_bytes < w.total)
         return fail(STL_ERR_WORKSPACE, "stl_mlp_forward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);

@@ -141,3 +141,23 @@ def test_weight_encoding_backward_argument_checks():
         with pytest.raises(stl.StlError) as e:
             stl.stl_encode_weight_backward(prob, *args, stream=0)
         assert e.value.status == status
+
+
+def test_misaligned_pointers_are_rejected():
+    """Data pointers must be 16-byte aligned; the check comes before any launch."""
+    prob = stl.Problem(256, 256, 256, 32, stl.STL_BF16)
+    odd = FAKE + 8
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_forward(prob, odd, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 1 << 40, 0, stream=0)
+    assert e.value.status == 1 and "aligned" in str(e.value)
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_backward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, odd, FAKE, 0, FAKE, 1 << 40, stream=0)
+    assert e.value.status == 1 and "aligned" in str(e.value)
+    for fn, args in ((stl.stl_encode_weight, (FAKE, odd, FAKE)), (stl.stl_encode_activation, (FAKE, FAKE, odd)),
+                     (stl.stl_plane_matmul, (odd, FAKE, FAKE))):
+        with pytest.raises(stl.StlError) as e:
+            fn(prob, *args, stream=0)
+        assert e.value.status == 1
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_decode(prob, FAKE, FAKE, odd, 0, stream=0)
+    assert e.value.status == 1

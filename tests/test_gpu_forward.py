@@ -153,6 +153,25 @@ def test_config2_full_size(gu):
     assert 0.2 < C.var() / (32 / 64) < 5.0
 
 
+@pytest.mark.parametrize("r", [8, 16, 24, 49, 64])
+def test_config3_rank_sweep_full_size(gu, r):
+    """bf16, m=8192, k=n=4096 at every rank of the sweep (r = 32 is the forward+backward workload's test): output
+    rows are independent, so whole row slabs are checked against the plane oracle run on those rows of X alone,
+    and sampled 8x8-tile blocks against literal Eq. (2)."""
+    p = stl_synth.stl_problem(8192, 4096, 4096, r, seed=stl_synth.SEEDS["C3"] + 100 * r, dtype="bf16")
+    C = gu.forward(p, "bf16")
+    assert np.isfinite(C).all()
+    for r0, r1 in ((0, 256), (4096 - 128, 4096 + 128), (8192 - 64, 8192)):
+        ref = planes.forward(p["X"][r0:r1], p["What"], p["E_X"], p["D"])
+        assert gu.rel(C[r0:r1], ref) <= gu.TOL["bf16"], (r0, r1)
+    rng = np.random.default_rng(r)
+    for _ in range(2):
+        I0, J0 = int(rng.integers(0, 2048 - 8)), int(rng.integers(0, 1024 - 8))
+        blk = oracle.forward_block(p["X"], p["What"], p["E_X"], p["D"], I0, I0 + 8, J0, J0 + 8)
+        assert gu.rel(C[4 * I0:4 * I0 + 32, 4 * J0:4 * J0 + 32], blk) <= 2 * gu.TOL["bf16"]
+    assert 0.2 < C.var() / (r / 64) < 5.0
+
+
 def test_forward_is_deterministic(gu):
     p = stl_synth.stl_problem(512, 512, 512, 32, seed=77, dtype="bf16")
     a = gu.forward(p, "bf16")

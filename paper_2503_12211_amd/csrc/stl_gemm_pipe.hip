@@ -216,8 +216,16 @@ __device__ unsigned long long g_timeline[8192 * 4];
 template <int WAVES_M, int WAVES_N, int NS, int SWZ, bool A_T, bool B_T, typename TO, bool ACC>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B,
                                                         TO *__restrict__ Out, int Mi, int Nj, int Kl, int tiles_m,
-                                                        int tiles_n, int total, int dbg)
+                                                        int tiles_n, int total, int dbg_arg)
 {
+    // Timing-only ablation switches (they skip parts of the kernel and give wrong results): compiled in only with
+    // -DSTL_GEMM_ABLATE; in the normal build dbg is the constant 0 and every test below folds away.
+#ifdef STL_GEMM_ABLATE
+    const int dbg = dbg_arg;
+#else
+    constexpr int dbg = 0;
+    (void)dbg_arg;
+#endif
     using namespace pipe;
     constexpr int BM = 256, BN = 256, NW = WAVES_M * WAVES_N, WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int FM = WM / 32, FN = WN / 32;
@@ -469,7 +477,11 @@ static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *
     static const bool persist = []() { const char *e = getenv("STL_GEMM_PERSIST"); return !e || atoi(e) != 0; }();
     const int cus = cu_count();
     const unsigned grid = (unsigned)((persist && total > cus) ? cus : total);
+#ifdef STL_GEMM_ABLATE
     static const int dbg = []() { const char *e = getenv("STL_GEMM_DBG"); return e ? atoi(e) : 0; }();
+#else
+    const int dbg = 0;
+#endif
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), smem, s, (const bf16_t *)A, (const bf16_t *)B, (TO *)Out, g.Mi, g.Nj,
                        g.Kl, tiles_m, tiles_n, (int)total, dbg);
     return hipGetLastError();

@@ -6,11 +6,12 @@ addresses go in, the status code is checked, nothing is computed here.
 from __future__ import annotations
 
 import ctypes
+import os
 from dataclasses import dataclass
 from pathlib import Path
 
 _HERE = Path(__file__).resolve().parent
-_LIB_PATH = _HERE / "libstl_mi355x.so"
+_LIB_PATH = Path(os.environ.get("STL_LIBRARY", _HERE / "libstl_mi355x.so"))   # STL_LIBRARY: another build of the library
 
 STL_F32, STL_BF16 = 0, 1
 STL_OP_ENCODE_WEIGHT, STL_OP_FORWARD, STL_OP_BACKWARD, STL_OP_ENCODE_WEIGHT_BACKWARD = 0, 1, 2, 3

@@ -307,13 +307,16 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
 #pragma unroll
         for (int b = 0; b < FN; ++b) vb[0][b] = fb.read(smem + OPER_BYTES, b, 0);
 
-        for (int s = 0; s < nks; ++s) {
+        // One stage (two k16-steps).  REFILL: stage s+NS-1 is fetched into the slot freed by stage s-1 -- a compile-time
+        // switch, so that the loop over the stages that refill carries no test around the DMA instructions.
+        auto stage = [&](int s, auto refill_c) {
+            constexpr bool REFILL = decltype(refill_c)::value;
             if (s + 1 < nks && !(dbg & 8)) {
-                if (s + NS - 2 < nks) wait_vmcnt<DMA_PER_STAGE * (NS - 3)>();
+                if (REFILL || s + NS - 2 < nks) wait_vmcnt<DMA_PER_STAGE * (NS - 3)>();
                 else wait_vmcnt<0>();
             }
             if (!(dbg & 4)) block_barrier();   // stage s+1 visible to all; nobody reads stage s-1 any more
-            const bool refill = s + NS - 1 < nks && !(dbg & 16);
+            const bool refill = REFILL && !(dbg & 16);
             const uint32_t dst = smem_lds + ((s + NS - 1) % NS) * STAGE_BYTES;
             const char *cur = smem + (s % NS) * STAGE_BYTES;
             const char *nxt = smem + ((s + 1) % NS) * STAGE_BYTES;
@@ -322,8 +325,9 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
             // this wavefront's share of the refill DMA is issued one instruction at a time further down.  Issuing
             // the DMA in one burst right after the barrier backs up the vector-memory queue of all eight
             // wavefronts at once and holds their MFMAs behind it; the fences pin the interleaving.
-            auto step = [&](auto par_c, const char *src, int ks, bool a_side) {
+            auto step = [&](auto par_c, const char *src, int ks, auto a_side_c) {
                 constexpr int par = decltype(par_c)::value;
+                constexpr bool a_side = decltype(a_side_c)::value;
                 static_for<0, FM * FN>([&](auto i_c) {
                     constexpr int i = decltype(i_c)::value, a = i / FN, b = i % FN;
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[par][b], va[par][a], acc[a][b], 0, 0, 0);
@@ -343,13 +347,13 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     }
-                    if constexpr (i >= 2 && (i % 2) == 0) {
+                    if constexpr (REFILL && i >= 2 && (i % 2) == 0) {
                         constexpr int j = (i - 2) / 2;       // DMA slot inside this step
                         if (refill) {
-                            if (a_side) {
-                                if (j < decltype(sa)::NI) sa.issue_one(dst, wave, j);
+                            if constexpr (a_side) {
+                                if constexpr (j < decltype(sa)::NI) sa.issue_one(dst, wave, j);
                             } else {
-                                if (j < decltype(sb)::NI) sb.issue_one(dst + OPER_BYTES, wave, j);
+                                if constexpr (j < decltype(sb)::NI) sb.issue_one(dst + OPER_BYTES, wave, j);
                             }
                         }
                         __builtin_amdgcn_sched_barrier(0);
@@ -358,9 +362,12 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
             };
             // step 0 of stage s (fetch step 1 of stage s; refill the A operand), then step 1 (fetch step 0 of stage
             // s+1 -- after the last stage that reads a stale ring slot whose values are never used; refill B)
-            step(std::integral_constant<int, 0>{}, cur, 1, true);
-            step(std::integral_constant<int, 1>{}, nxt, 0, false);
-        }
+            step(std::integral_constant<int, 0>{}, cur, 1, std::true_type{});
+            step(std::integral_constant<int, 1>{}, nxt, 0, std::false_type{});
+        };
+        const int n_refill = nks > NS - 1 ? nks - (NS - 1) : 0;
+        for (int s = 0; s < n_refill; ++s) stage(s, std::true_type{});
+        for (int s = n_refill; s < nks; ++s) stage(s, std::false_type{});
 
         // every wavefront is done with the ring: refill it for the next block before storing this one
         block_barrier();

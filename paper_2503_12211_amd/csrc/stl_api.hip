@@ -356,10 +356,26 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
         return STL_OK;
     }
     void *yhat = Yhat_save ? Yhat_save : (void *)(base + w.yhat);
-    STL_HIP(stl::launch_encode(prob->dtype, X, E_X, xhat, d.M, d.K, d.r, s), "forward/encode");
-    stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false};
-    STL_HIP(stl::launch_plane_gemm(prob->dtype, g, xhat, What, yhat, s), "forward/plane products");
-    STL_HIP(stl::launch_decode(prob->dtype, yhat, D, C, d.M, d.N, d.r, gelu, s), "forward/decode");
+    // Output rows are independent, so when neither plane tensor is handed back the rows can be taken in slabs that
+    // reuse the same plane scratch: the planes of a slab are then still in the 256 MB last-level cache when the next
+    // kernel reads them, instead of having been pushed out by the rest of a large problem.  A slab holds about 128 MB
+    // of planes, in multiples of the plane products' 256-row blocks, and at least 1024 tile rows.
+    int slab_rows = d.M;
+    const size_t row_bytes = (size_t)d.r * ((size_t)d.K + d.N) * d.es;      // Xhat + Yhat bytes per tile row
+    if (!Xhat_save && !Yhat_save && row_bytes * d.M > ((size_t)192 << 20)) {
+        const size_t fit = ((size_t)128 << 20) / row_bytes;                 // tile rows whose planes take 128 MB
+        // shorter slabs than 1024 tile rows cost the plane products more than the cache gives back (measured)
+        if (fit >= 1024 && (int)(fit / 256) * 256 < d.M) slab_rows = (int)(fit / 256) * 256;
+    }
+    for (int r0 = 0; r0 < d.M; r0 += slab_rows) {
+        const int rows = d.M - r0 < slab_rows ? d.M - r0 : slab_rows;
+        const char *Xs = (const char *)X + (size_t)r0 * 4 * prob->k * d.es;
+        char *Cs = (char *)C + (size_t)r0 * 4 * prob->n * d.es;
+        STL_HIP(stl::launch_encode(prob->dtype, Xs, E_X, xhat, rows, d.K, d.r, s), "forward/encode");
+        stl::GemmDesc g{rows, d.N, d.K, d.r, false, true, false, false};
+        STL_HIP(stl::launch_plane_gemm(prob->dtype, g, xhat, What, yhat, s), "forward/plane products");
+        STL_HIP(stl::launch_decode(prob->dtype, yhat, D, Cs, rows, d.N, d.r, gelu, s), "forward/decode");
+    }
     return STL_OK;
 }
 

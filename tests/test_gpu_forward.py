@@ -172,6 +172,20 @@ def test_config3_rank_sweep_full_size(gu, r):
     assert 0.2 < C.var() / (r / 64) < 5.0
 
 
+def test_forward_row_slabs_with_ragged_tail(gu):
+    """m = 8736 (2184 tile rows), k = n = 4096, r = 32 without saved planes: the forward takes 1024-tile-row slabs that
+    share the plane scratch, the last one 136 tile rows long; rows around every slab boundary and the tail are checked
+    against the plane oracle run on those rows alone, and the result must equal the single-pass result bit for bit."""
+    p = stl_synth.stl_problem(8736, 4096, 4096, 32, seed=4321, dtype="bf16")
+    C = gu.forward(p, "bf16")
+    assert np.isfinite(C).all()
+    for r0, r1 in ((0, 64), (4096 - 64, 4096 + 64), (8192 - 64, 8192 + 64), (8736 - 100, 8736)):
+        ref = planes.forward(p["X"][r0:r1], p["What"], p["E_X"], p["D"])
+        assert gu.rel(C[r0:r1], ref) <= gu.TOL["bf16"], (r0, r1)
+    C1, _ = gu.forward(p, "bf16", save_yhat=True)              # saving Yhat keeps the whole problem in one pass
+    assert np.array_equal(C, C1)
+
+
 def test_forward_is_deterministic(gu):
     p = stl_synth.stl_problem(512, 512, 512, 32, seed=77, dtype="bf16")
     a = gu.forward(p, "bf16")

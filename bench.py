@@ -249,6 +249,24 @@ def main():
     ms_gemm = T.events(lambda: stl.stl_plane_matmul(prob, Xhat, What, Yhat), S, W)
     ms_dec = T.events(lambda: stl.stl_decode(prob, Yhat, D, C), S, W)
 
+    # the same stages cache-cold: three buffer sets in rotation (each call touches more than the 256 MB last-level cache
+    # holds before a buffer comes round again)
+    sets = [(X, Xhat, Yhat, C)] + [(torch.randn_like(X), torch.empty_like(Xhat), torch.randn_like(Yhat), torch.empty_like(C))
+                                   for _ in range(2)]
+    rot = {"i": 0}
+
+    def rotate(fn):
+        def call():
+            xs = sets[rot["i"] % 3]
+            rot["i"] += 1
+            fn(*xs)
+        return call
+    S3 = max(3 * (S // 3), 3)
+    ms_enc_cold = T.events(rotate(lambda x, xh, yh, c: stl.stl_encode_activation(prob, x, E_X, xh)), S3, 3)
+    ms_gemm_cold = T.events(rotate(lambda x, xh, yh, c: stl.stl_plane_matmul(prob, xh, What, yh)), S3, 3)
+    ms_dec_cold = T.events(rotate(lambda x, xh, yh, c: stl.stl_decode(prob, yh, D, c)), S3, 3)
+    del sets
+
     gemm_flop, fwd_flop, bwd_flop = flops_model(m, k, n, r)
     dense_flop = 2.0 * m * k * n
     tf = lambda fl, ms: fl / (ms * 1e-3) / 1e12
@@ -259,6 +277,8 @@ def main():
     log(f"  STL  fwd {ms_fwd:.4f} ms  bwd {ms_bwd:.4f} ms  step {ms_step:.4f} ms  "
         f"({tf(fwd_flop + bwd_flop, ms_step):.1f} TFLOP/s executed)")
     log(f"  dense fwd {ms_dense_fwd:.4f} ms ({tf(dense_flop, ms_dense_fwd):.1f} TFLOP/s)  step {ms_dense_step:.4f} ms")
+    log(f"  stages, cache-cold rotation: encode {ms_enc_cold:.4f} ms ({enc_bytes / ms_enc_cold / 1e6:.0f} GB/s)  plane products "
+        f"{ms_gemm_cold:.4f} ms ({tf(gemm_flop, ms_gemm_cold):.1f} TFLOP/s)  decode {ms_dec_cold:.4f} ms ({dec_bytes / ms_dec_cold / 1e6:.0f} GB/s)")
     log(f"  stages: encode {ms_enc:.4f} ms ({enc_bytes / ms_enc / 1e6:.0f} GB/s)  plane products {ms_gemm:.4f} ms "
         f"({tf(gemm_flop, ms_gemm):.1f} TFLOP/s, {100 * tf(gemm_flop, ms_gemm) / PEAK_BF16_TFLOPS:.1f}% of bf16 peak)  "
         f"decode {ms_dec:.4f} ms ({dec_bytes / ms_dec / 1e6:.0f} GB/s)")
@@ -285,6 +305,11 @@ def main():
             "plane_products": {"ms": round(ms_gemm, 5), "TFLOPs": round(tf(gemm_flop, ms_gemm), 2)},
             "decode": {"ms": round(ms_dec, 5), "GBps": round(dec_bytes / ms_dec / 1e6, 1),
                        "frac_hbm_peak": round(dec_bytes / ms_dec / 1e6 / PEAK_HBM_GBS, 4)},
+        },
+        "stages_cache_cold": {
+            "encode": {"ms": round(ms_enc_cold, 5), "GBps": round(enc_bytes / ms_enc_cold / 1e6, 1)},
+            "plane_products": {"ms": round(ms_gemm_cold, 5), "TFLOPs": round(tf(gemm_flop, ms_gemm_cold), 2)},
+            "decode": {"ms": round(ms_dec_cold, 5), "GBps": round(dec_bytes / ms_dec_cold / 1e6, 1)},
         },
         "roofline": {"kernel": "gemm_pipe_kernel (forward plane products Yhat[p] = Xhat[p] What[p], one launch, "
                                "2*r*M*K*N flops)", "bound": "mfma",

@@ -154,8 +154,8 @@ def main():
     X, What, E_X, D, dC = (dev(p[s]) for s in ("X", "What", "E_X", "D", "dC"))
     prob = stl.Problem(m, k, n, r, stl.STL_BF16)
     C = torch.empty((m, n), dtype=bf, device="cuda")
-    Yhat = torch.empty((r, M, N), dtype=bf, device="cuda")
-    Xhat = torch.empty((r, M, K), dtype=bf, device="cuda")
+    Yhat = torch.empty(stl.stl_plane_elems(M, N, r), dtype=bf, device="cuda")      # grouped layout, see include/stl.h
+    Xhat = torch.empty(stl.stl_plane_elems(M, K, r), dtype=bf, device="cuda")
     dX = torch.empty((m, k), dtype=bf, device="cuda")
     dWhat = torch.empty((r, K, N), dtype=torch.float32, device="cuda")
     dE_X = torch.empty((r, 16), dtype=torch.float32, device="cuda")

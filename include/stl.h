@@ -16,7 +16,15 @@
  *  - All matrices are dense, row-major, without strides.  vec() of a tile is
  *    row-major: vec(T)[a*t+b] = T[a][b].  E_X, E_W, D are r x t^2 row-major
  *    (Definition 3.1); the decoder is applied as D^T.
- *  - Plane tensors (What, Xhat, Yhat, dWhat) are plane-major: [p][row tile][col tile].
+ *  - Weight-side plane tensors (What, dWhat) are plane-major: [p][row tile][col tile].
+ *  - Activation-side plane tensors (Xhat, Yhat; the library's dYhat and dXhat scratch alike) are plane-major
+ *    within groups of STL_PLANE_GROUP = 64 tile rows: element (p, I, J) of an r x R x Cc tensor lives at
+ *        ((I / 64) * r + p) * 64 * Cc + (I % 64) * Cc + J,
+ *    and a buffer holds stl_plane_elems(R, Cc, r) = r * roundup(R, 64) * Cc elements.  (The r segments of
+ *    one tile row then lie within r * 64 * Cc elements of each other instead of a whole plane apart, which
+ *    the encode / decode passes need for speed, while 64 consecutive rows of a plane stay contiguous for
+ *    the plane products.)  Callers that only pass Xhat_save / Yhat_save from stl_forward to stl_backward
+ *    never need to know.
  *  - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned
  *    (STL_ERR_INVALID_ARG otherwise).
  *    The library allocates and frees no device memory: scratch comes from `ws`
@@ -60,6 +68,10 @@ typedef struct {
     int32_t dtype;     /* stl_dtype_t */
 } stl_problem_t;
 
+#define STL_PLANE_GROUP 64
+/* Elements of an activation-side plane tensor with r planes of R x Cc tiles (rows rounded up to the group). */
+size_t stl_plane_elems(int64_t R, int64_t Cc, int r);
+
 /* which operation a workspace is sized for */
 enum { STL_OP_ENCODE_WEIGHT = 0, STL_OP_FORWARD = 1, STL_OP_BACKWARD = 2, STL_OP_ENCODE_WEIGHT_BACKWARD = 3 };
 
@@ -100,9 +112,9 @@ stl_status_t stl_encode_weight_backward(const stl_problem_t *prob, const void *W
 /*
  * Forward C = X <> W (Definition 3.1 / Eq. (2); Algorithm 1).
  * X: m x k (in).  What: r x K x N (in).  E_X, D: r x 16 (in).  C: m x n (out).
- * Xhat_save: NULL, or r x M x K (out, storage dtype): the encoded activations of step (i) are
+ * Xhat_save: NULL, or stl_plane_elems(M, K, r) elements (out, storage dtype, grouped layout): the encoded activations of step (i) are
  *   written there instead of into the workspace, for stl_backward.
- * Yhat_save: NULL, or r x M x N (out, storage dtype): the encoded output
+ * Yhat_save: NULL, or stl_plane_elems(M, N, r) elements (out, storage dtype, grouped layout): the encoded output
  *   Yhat[p] = Xhat[p] * What[p] (Claim 3.4) is also written there, for stl_backward.
  * ws / ws_bytes: scratch of at least stl_workspace_bytes(prob, STL_OP_FORWARD, flags).
  */

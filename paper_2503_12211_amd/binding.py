@@ -20,7 +20,7 @@ STL_FLAG_GELU = 0x100
 
 # every symbol include/stl.h declares
 SYMBOLS = (
-    "stl_workspace_bytes", "stl_encode_weight", "stl_encode_weight_backward", "stl_forward", "stl_backward", "stl_encode_activation",
+    "stl_plane_elems", "stl_workspace_bytes", "stl_encode_weight", "stl_encode_weight_backward", "stl_forward", "stl_backward", "stl_encode_activation",
     "stl_plane_matmul", "stl_decode", "stl_mlp_workspace_bytes", "stl_mlp_forward", "stl_recode",
     "stl_status_string", "stl_last_error", "stl_version",
 )
@@ -67,6 +67,8 @@ def _load():
                            "(there is no fallback path)")
     lib = ctypes.CDLL(str(_LIB_PATH))
     pp = ctypes.POINTER(_CProblem)
+    lib.stl_plane_elems.restype = ctypes.c_size_t
+    lib.stl_plane_elems.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
     lib.stl_workspace_bytes.restype = ctypes.c_size_t
     lib.stl_workspace_bytes.argtypes = [pp, ctypes.c_int, ctypes.c_int]
     lib.stl_encode_weight.argtypes = [pp, _P, _P, _P, _P]
@@ -129,6 +131,13 @@ def stl_last_error() -> str:
 
 def stl_version() -> str:
     return _load().stl_version().decode()
+
+
+STL_PLANE_GROUP = 64
+
+
+def stl_plane_elems(R: int, Cc: int, r: int) -> int:
+    return int(_load().stl_plane_elems(R, Cc, r))
 
 
 def stl_workspace_bytes(prob: Problem, op: int, flags: int = 0) -> int:

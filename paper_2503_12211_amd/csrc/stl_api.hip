@@ -28,7 +28,11 @@ stl_status_t hip_fail(hipError_t e, const char *what)
 struct Dims {
     int M, K, N, r;
     size_t es;  // element size of the storage dtype
+    // activation-side plane tensors are stored in groups of kPlaneGroup tile rows: their row count rounded up
+    size_t Mp() const { return ((size_t)M + stl::kPlaneGroup - 1) / stl::kPlaneGroup * stl::kPlaneGroup; }
 };
+
+constexpr int PG = stl::kPlaneGroup;   // layout of Xhat, Yhat, dYhat, dXhat; What and dWhat are plane-major (0)
 
 constexpr int64_t kMaxDim = (int64_t)1 << 24;  // per-dimension cap; keeps tile indices in int
 
@@ -85,9 +89,9 @@ FwdWs fwd_layout(const Dims &d, int variant)
     FwdWs w{};
     size_t off = 0;
     w.xhat = off;
-    if (variant != STL_FLAG_FUSED) off += align256((size_t)d.r * d.M * d.K * d.es);
+    if (variant != STL_FLAG_FUSED) off += align256((size_t)d.r * d.Mp() * d.K * d.es);
     w.yhat = off;
-    if (variant == STL_FLAG_AUTO || variant == STL_FLAG_UNFUSED) off += align256((size_t)d.r * d.M * d.N * d.es);
+    if (variant == STL_FLAG_AUTO || variant == STL_FLAG_UNFUSED) off += align256((size_t)d.r * d.Mp() * d.N * d.es);
     w.total = off;
     return w;
 }
@@ -100,7 +104,7 @@ BwdWs bwd_layout(const Dims &d)
 {
     BwdWs w{};
     size_t off = 0;
-    const size_t pk = align256((size_t)d.r * d.M * d.K * d.es), pn = align256((size_t)d.r * d.M * d.N * d.es);
+    const size_t pk = align256((size_t)d.r * d.Mp() * d.K * d.es), pn = align256((size_t)d.r * d.Mp() * d.N * d.es);
     w.xhat = off;
     off += pk;
     w.dyhat = off;
@@ -176,13 +180,13 @@ MlpWs mlp_layout(const stl_problem_t *up, const Dims &d1, const Dims &d2, int va
     MlpWs w{};
     size_t off = 0;
     w.xhat1 = off;
-    off += align256((size_t)d1.r * d1.M * d1.K * d1.es);
+    off += align256((size_t)d1.r * d1.Mp() * d1.K * d1.es);
     w.yhat1 = off;
-    off += align256((size_t)d1.r * d1.M * d1.N * d1.es);
+    off += align256((size_t)d1.r * d1.Mp() * d1.N * d1.es);
     w.xhat2 = off;
-    off += align256((size_t)d2.r * d2.M * d2.K * d2.es);
+    off += align256((size_t)d2.r * d2.Mp() * d2.K * d2.es);
     w.yhat2 = off;
-    off += align256((size_t)d2.r * d2.M * d2.N * d2.es);
+    off += align256((size_t)d2.r * d2.Mp() * d2.N * d2.es);
     w.one_pass = variant == STL_FLAG_AUTO && stl::recode_eligible(up->dtype, d1.N);
     w.hidden = off;
     if (!w.one_pass) off += align256((size_t)up->m * up->n * d1.es);
@@ -214,7 +218,13 @@ const char *stl_status_string(stl_status_t s)
 
 const char *stl_last_error(void) { return g_err; }
 
-const char *stl_version(void) { return "0.1.0 gfx950"; }
+const char *stl_version(void) { return "0.2.0 gfx950"; }
+
+size_t stl_plane_elems(int64_t R, int64_t Cc, int r)
+{
+    if (R < 0 || Cc < 0 || r < 0) return 0;
+    return (size_t)r * (size_t)((R + PG - 1) / PG * PG) * (size_t)Cc;
+}
 
 size_t stl_workspace_bytes(const stl_problem_t *prob, int op, int flags)
 {
@@ -241,7 +251,7 @@ stl_status_t stl_encode_weight(const stl_problem_t *prob, const void *W, const v
     if (st != STL_OK) return st;
     if (!W || !E_W || !What) return fail(STL_ERR_INVALID_ARG, "stl_encode_weight: NULL pointer");
     if (any_misaligned(W, E_W, What)) return fail(STL_ERR_INVALID_ARG, "stl_encode_weight: pointer not 16-byte aligned");
-    STL_HIP(stl::launch_encode(prob->dtype, W, E_W, What, d.K, d.N, d.r, (hipStream_t)stream), "encode_weight");
+    STL_HIP(stl::launch_encode(prob->dtype, W, E_W, What, d.K, d.N, d.r, 0, (hipStream_t)stream), "encode_weight");
     return STL_OK;
 }
 
@@ -271,13 +281,13 @@ stl_status_t stl_encode_weight_backward(const stl_problem_t *prob, const void *W
         planes = base + w.planes;
     }
     if (dW && dE_W && stl::decode_outer_eligible(dt, d.N)) {
-        STL_HIP(stl::launch_decode_outer(planes, E_W, dW, W, dE_W, part, d.K, d.N, d.r, accumulate, s),
+        STL_HIP(stl::launch_decode_outer(planes, E_W, dW, W, dE_W, part, d.K, d.N, d.r, accumulate, 0, s),
                 "encode_weight_backward/dW + dE_W");
         return STL_OK;
     }
-    if (dW) STL_HIP(stl::launch_decode(dt, planes, E_W, dW, d.K, d.N, d.r, false, s), "encode_weight_backward/dW");
+    if (dW) STL_HIP(stl::launch_decode(dt, planes, E_W, dW, d.K, d.N, d.r, false, 0, s), "encode_weight_backward/dW");
     if (dE_W)
-        STL_HIP(stl::launch_outer_reduce(dt, planes, W, dE_W, part, d.K, d.N, d.r, accumulate, s), "encode_weight_backward/dE_W");
+        STL_HIP(stl::launch_outer_reduce(dt, planes, W, dE_W, part, d.K, d.N, d.r, accumulate, 0, s), "encode_weight_backward/dE_W");
     return STL_OK;
 }
 
@@ -288,7 +298,7 @@ stl_status_t stl_encode_activation(const stl_problem_t *prob, const void *X, con
     if (st != STL_OK) return st;
     if (!X || !E_X || !Xhat) return fail(STL_ERR_INVALID_ARG, "stl_encode_activation: NULL pointer");
     if (any_misaligned(X, E_X, Xhat)) return fail(STL_ERR_INVALID_ARG, "stl_encode_activation: pointer not 16-byte aligned");
-    STL_HIP(stl::launch_encode(prob->dtype, X, E_X, Xhat, d.M, d.K, d.r, (hipStream_t)stream), "encode_activation");
+    STL_HIP(stl::launch_encode(prob->dtype, X, E_X, Xhat, d.M, d.K, d.r, PG, (hipStream_t)stream), "encode_activation");
     return STL_OK;
 }
 
@@ -299,7 +309,7 @@ stl_status_t stl_plane_matmul(const stl_problem_t *prob, const void *Xhat, const
     if (st != STL_OK) return st;
     if (!Xhat || !What || !Yhat) return fail(STL_ERR_INVALID_ARG, "stl_plane_matmul: NULL pointer");
     if (any_misaligned(Xhat, What, Yhat)) return fail(STL_ERR_INVALID_ARG, "stl_plane_matmul: pointer not 16-byte aligned");
-    stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false};
+    stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false, PG, 0, PG};
     STL_HIP(stl::launch_plane_gemm(prob->dtype, g, Xhat, What, Yhat, (hipStream_t)stream), "plane_matmul");
     return STL_OK;
 }
@@ -312,7 +322,7 @@ stl_status_t stl_decode(const stl_problem_t *prob, const void *Yhat, const void 
     if (!Yhat || !D || !C) return fail(STL_ERR_INVALID_ARG, "stl_decode: NULL pointer");
     if (any_misaligned(Yhat, D, C)) return fail(STL_ERR_INVALID_ARG, "stl_decode: pointer not 16-byte aligned");
     if (flags & ~STL_FLAG_GELU) return fail(STL_ERR_UNSUPPORTED, "stl_decode: unknown flag bits 0x%x", flags);
-    STL_HIP(stl::launch_decode(prob->dtype, Yhat, D, C, d.M, d.N, d.r, (flags & STL_FLAG_GELU) != 0, (hipStream_t)stream),
+    STL_HIP(stl::launch_decode(prob->dtype, Yhat, D, C, d.M, d.N, d.r, (flags & STL_FLAG_GELU) != 0, PG, (hipStream_t)stream),
             "decode");
     return STL_OK;
 }
@@ -345,13 +355,13 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
     char *base = (char *)ws;
 
     if (variant == STL_FLAG_FUSED) {
-        STL_HIP(stl::launch_block_forward(true, X, What, E_X, D, C, Yhat_save, d.M, d.K, d.N, d.r, gelu, s), "forward/fused");
+        STL_HIP(stl::launch_block_forward(true, X, What, E_X, D, C, Yhat_save, d.M, d.K, d.N, d.r, gelu, PG, s), "forward/fused");
         return STL_OK;
     }
     void *xhat = Xhat_save ? Xhat_save : (void *)(base + w.xhat);
     if (variant == STL_FLAG_EPILOGUE) {
-        STL_HIP(stl::launch_encode(prob->dtype, X, E_X, xhat, d.M, d.K, d.r, s), "forward/encode");
-        STL_HIP(stl::launch_block_forward(false, xhat, What, E_X, D, C, Yhat_save, d.M, d.K, d.N, d.r, gelu, s),
+        STL_HIP(stl::launch_encode(prob->dtype, X, E_X, xhat, d.M, d.K, d.r, PG, s), "forward/encode");
+        STL_HIP(stl::launch_block_forward(false, xhat, What, E_X, D, C, Yhat_save, d.M, d.K, d.N, d.r, gelu, PG, s),
                 "forward/plane products + decode");
         return STL_OK;
     }
@@ -371,10 +381,10 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
         const int rows = d.M - r0 < slab_rows ? d.M - r0 : slab_rows;
         const char *Xs = (const char *)X + (size_t)r0 * 4 * prob->k * d.es;
         char *Cs = (char *)C + (size_t)r0 * 4 * prob->n * d.es;
-        STL_HIP(stl::launch_encode(prob->dtype, Xs, E_X, xhat, rows, d.K, d.r, s), "forward/encode");
-        stl::GemmDesc g{rows, d.N, d.K, d.r, false, true, false, false};
+        STL_HIP(stl::launch_encode(prob->dtype, Xs, E_X, xhat, rows, d.K, d.r, PG, s), "forward/encode");
+        stl::GemmDesc g{rows, d.N, d.K, d.r, false, true, false, false, PG, 0, PG};
         STL_HIP(stl::launch_plane_gemm(prob->dtype, g, xhat, What, yhat, s), "forward/plane products");
-        STL_HIP(stl::launch_decode(prob->dtype, yhat, D, Cs, rows, d.N, d.r, gelu, s), "forward/decode");
+        STL_HIP(stl::launch_decode(prob->dtype, yhat, D, Cs, rows, d.N, d.r, gelu, PG, s), "forward/decode");
     }
     return STL_OK;
 }
@@ -403,37 +413,37 @@ stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *
 
     const bool need_xhat = dWhat || (dD && !Yhat_saved);
     if (need_xhat && !Xhat_saved)
-        STL_HIP(stl::launch_encode(dt, X, E_X, base + w.xhat, d.M, d.K, d.r, s), "backward/encode X");
+        STL_HIP(stl::launch_encode(dt, X, E_X, base + w.xhat, d.M, d.K, d.r, PG, s), "backward/encode X");
     const void *yhat = Yhat_saved;
     if (dD && !yhat) {
-        stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false};
+        stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false, PG, 0, PG};
         STL_HIP(stl::launch_plane_gemm(dt, g, xhat, What, base + w.yhat, s), "backward/recompute Yhat");
         yhat = base + w.yhat;
     }
     if (dD && stl::encode_outer_eligible(dt, d.N)) {
         // one pass over dC: dYhat = encode with D, dD = sum over tiles of Yhat (x) dc
-        STL_HIP(stl::launch_encode_outer(dC, D, dyhat, yhat, dD, part, d.M, d.N, d.r, accumulate, s), "backward/dYhat + dD");
+        STL_HIP(stl::launch_encode_outer(dC, D, dyhat, yhat, dD, part, d.M, d.N, d.r, accumulate, PG, s), "backward/dYhat + dD");
     } else {
-        STL_HIP(stl::launch_encode(dt, dC, D, dyhat, d.M, d.N, d.r, s), "backward/encode dC");
-        if (dD) STL_HIP(stl::launch_outer_reduce(dt, yhat, dC, dD, part, d.M, d.N, d.r, accumulate, s), "backward/dD");
+        STL_HIP(stl::launch_encode(dt, dC, D, dyhat, d.M, d.N, d.r, PG, s), "backward/encode dC");
+        if (dD) STL_HIP(stl::launch_outer_reduce(dt, yhat, dC, dD, part, d.M, d.N, d.r, accumulate, PG, s), "backward/dD");
     }
     if (dX || dE_X) {
         // dXhat[p] = dYhat[p] * What[p]^T : contraction over J, What[p] is stored [L][J]
-        stl::GemmDesc g{d.M, d.K, d.N, d.r, false, false, false, false};
+        stl::GemmDesc g{d.M, d.K, d.N, d.r, false, false, false, false, PG, 0, PG};
         STL_HIP(stl::launch_plane_gemm(dt, g, dyhat, What, dxhat, s), "backward/dXhat");
     }
     if (dWhat) {
         // dWhat[p] = Xhat[p]^T * dYhat[p] : contraction over I, both operands stored [I][.]
-        stl::GemmDesc g{d.K, d.N, d.M, d.r, true, true, true, accumulate != 0};
+        stl::GemmDesc g{d.K, d.N, d.M, d.r, true, true, true, accumulate != 0, PG, PG, 0};
         STL_HIP(stl::launch_plane_gemm(dt, g, xhat, dyhat, dWhat, s), "backward/dWhat");
     }
     if (dX && dE_X && stl::decode_outer_eligible(dt, d.K)) {
         // one pass over dXhat: dX = decode with E_X, dE_X = sum over tiles of dXhat (x) x
-        STL_HIP(stl::launch_decode_outer(dxhat, E_X, dX, X, dE_X, part, d.M, d.K, d.r, accumulate, s), "backward/dX + dE_X");
+        STL_HIP(stl::launch_decode_outer(dxhat, E_X, dX, X, dE_X, part, d.M, d.K, d.r, accumulate, PG, s), "backward/dX + dE_X");
     } else {
-        if (dX) STL_HIP(stl::launch_decode(dt, dxhat, E_X, dX, d.M, d.K, d.r, false, s), "backward/decode dX");
+        if (dX) STL_HIP(stl::launch_decode(dt, dxhat, E_X, dX, d.M, d.K, d.r, false, PG, s), "backward/decode dX");
         if (dE_X)
-            STL_HIP(stl::launch_outer_reduce(dt, dxhat, X, dE_X, part, d.M, d.K, d.r, accumulate, s), "backward/dE_X");
+            STL_HIP(stl::launch_outer_reduce(dt, dxhat, X, dE_X, part, d.M, d.K, d.r, accumulate, PG, s), "backward/dE_X");
     }
     return STL_OK;
 }
@@ -460,12 +470,12 @@ stl_status_t stl_recode(const stl_problem_t *up, const stl_problem_t *down, cons
     hipStream_t s = (hipStream_t)stream;
     const bool gelu = (flags & STL_FLAG_GELU) != 0;
     if (variant == STL_FLAG_AUTO && stl::recode_eligible(up->dtype, d1.N)) {
-        STL_HIP(stl::launch_recode(Yhat1, D1, E_X2, Xhat2, d1.M, d1.N, d1.r, d2.r, gelu, s), "recode");
+        STL_HIP(stl::launch_recode(Yhat1, D1, E_X2, Xhat2, d1.M, d1.N, d1.r, d2.r, gelu, PG, s), "recode");
         return STL_OK;
     }
     if (!H) return fail(STL_ERR_INVALID_ARG, "stl_recode: the two-launch form needs the hidden-activation scratch H");
-    STL_HIP(stl::launch_decode(up->dtype, Yhat1, D1, H, d1.M, d1.N, d1.r, gelu, s), "recode/decode");
-    STL_HIP(stl::launch_encode(up->dtype, H, E_X2, Xhat2, d2.M, d2.K, d2.r, s), "recode/encode");
+    STL_HIP(stl::launch_decode(up->dtype, Yhat1, D1, H, d1.M, d1.N, d1.r, gelu, PG, s), "recode/decode");
+    STL_HIP(stl::launch_encode(up->dtype, H, E_X2, Xhat2, d2.M, d2.K, d2.r, PG, s), "recode/encode");
     return STL_OK;
 }
 
@@ -493,19 +503,19 @@ stl_status_t stl_mlp_forward(const stl_problem_t *up, const stl_problem_t *down,
     char *base = (char *)ws;
     void *xhat1 = base + w.xhat1, *yhat1 = base + w.yhat1, *xhat2 = base + w.xhat2, *yhat2 = base + w.yhat2;
 
-    STL_HIP(stl::launch_encode(dt, X, E_X1, xhat1, d1.M, d1.K, d1.r, s), "pair/encode");
-    stl::GemmDesc g1{d1.M, d1.N, d1.K, d1.r, false, true, false, false};
+    STL_HIP(stl::launch_encode(dt, X, E_X1, xhat1, d1.M, d1.K, d1.r, PG, s), "pair/encode");
+    stl::GemmDesc g1{d1.M, d1.N, d1.K, d1.r, false, true, false, false, PG, 0, PG};
     STL_HIP(stl::launch_plane_gemm(dt, g1, xhat1, What1, yhat1, s), "pair/plane products 1");
     if (w.one_pass) {
-        STL_HIP(stl::launch_recode(yhat1, D1, E_X2, xhat2, d1.M, d1.N, d1.r, d2.r, gelu, s), "pair/decode-activation-encode");
+        STL_HIP(stl::launch_recode(yhat1, D1, E_X2, xhat2, d1.M, d1.N, d1.r, d2.r, gelu, PG, s), "pair/decode-activation-encode");
     } else {
         void *hid = base + w.hidden;
-        STL_HIP(stl::launch_decode(dt, yhat1, D1, hid, d1.M, d1.N, d1.r, gelu, s), "pair/decode 1");
-        STL_HIP(stl::launch_encode(dt, hid, E_X2, xhat2, d2.M, d2.K, d2.r, s), "pair/encode 2");
+        STL_HIP(stl::launch_decode(dt, yhat1, D1, hid, d1.M, d1.N, d1.r, gelu, PG, s), "pair/decode 1");
+        STL_HIP(stl::launch_encode(dt, hid, E_X2, xhat2, d2.M, d2.K, d2.r, PG, s), "pair/encode 2");
     }
-    stl::GemmDesc g2{d2.M, d2.N, d2.K, d2.r, false, true, false, false};
+    stl::GemmDesc g2{d2.M, d2.N, d2.K, d2.r, false, true, false, false, PG, 0, PG};
     STL_HIP(stl::launch_plane_gemm(dt, g2, xhat2, What2, yhat2, s), "pair/plane products 2");
-    STL_HIP(stl::launch_decode(dt, yhat2, D2, C, d2.M, d2.N, d2.r, false, s), "pair/decode 2");
+    STL_HIP(stl::launch_decode(dt, yhat2, D2, C, d2.M, d2.N, d2.r, false, PG, s), "pair/decode 2");
     return STL_OK;
 }
 

@@ -39,6 +39,18 @@ template <> struct Elem<bf16_t> {
     static __device__ __forceinline__ void st(bf16_t *p, float v) { *p = f32_to_bf16(v); }
 };
 
+// Plane tensors [p][tile row][tile column] are stored in groups of `pg` tile rows: element (p, I, J) of an
+// r x R x Cc tensor lives at ((I / pg) * r + p) * pg * Cc + (I % pg) * Cc + J.  pg = R is the plain plane-major
+// layout (weights and their gradients); the activation-side tensors use groups of 64 tile rows, which keeps the r
+// segments belonging to one tile row within r * 64 * Cc elements of each other instead of a whole plane apart
+// (the kernels that walk over all planes of a tile row run a fifth faster on it) and still leaves 64 consecutive
+// rows of a plane contiguous for the plane products.  Inside a group the distance between planes is pg * Cc.
+__host__ __device__ __forceinline__ size_t plane_row_base(int I, int pg, int r, int Cc)
+{
+    const int g = I / pg;
+    return ((size_t)g * r * pg + (size_t)(I - g * pg)) * Cc;
+}
+
 // erf-form GELU in fp32, h * Phi(h), branch-free.  Phi(h) = erfc(-h / sqrt 2) / 2 with the rational-exponential
 // approximation of Abramowitz & Stegun 7.1.26,  erfc(x) ~ (a1 s + ... + a5 s^5) exp(-x^2),  s = 1 / (1 + p x),  x >= 0,
 // whose absolute error is below 1.5e-7 (the library erff costs about three times the instructions and diverges on

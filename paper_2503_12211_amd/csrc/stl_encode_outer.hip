@@ -27,7 +27,7 @@ typedef short v4i16_t __attribute__((ext_vector_type(4)));
 template <int KC>   // KC = number of 32-plane groups (1: r <= 32, 2: r <= 64)
 __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ E,
                                                              bf16_t *__restrict__ P, const bf16_t *__restrict__ Qp,
-                                                             float *__restrict__ part, int R, int Cc, int r, int chunks)
+                                                             float *__restrict__ part, int R, int Cc, int r, int chunks, int pg)
 {
     constexpr int ROWB = 128;                               // bytes per plane row of the slab (64 tiles)
     __shared__ __align__(16) char sT_all[4][64 * 32];       // per wavefront: [tile][16 entries] bf16
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__res
     const int pr = lane >> 3, ch = lane & 7;                // loader role: plane within a group of 8, 8-tile chunk
     const int j = lane & 15, kq = lane >> 4;
     const int ng = (r + 15) >> 4;
-    const size_t ld = (size_t)Cc * 4, plane = (size_t)R * Cc;
+    const size_t ld = (size_t)Cc * 4, plane = (size_t)pg * Cc;
 
     // encoder fragments: lane (plane 16g + j, kq) holds E[plane][4kq + e] in K slots 8kq + e, e < 4; zeros above
     bf16x8_t eb[4];
@@ -74,6 +74,7 @@ __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__res
     u32x4_t qa[KC * 4];     // plane segments, loader role: plane 8*g8 + pr, tiles 8ch .. 8ch+7
     auto fetch = [&](int Ii, int cki) {
         const int J0 = cki * 64;
+        const size_t rowb = Ii < R ? plane_row_base(Ii, pg, r, Cc) : 0;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             u32x2_t v = {0u, 0u};
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__res
         for (int g8 = 0; g8 < KC * 4; ++g8) {
             const int pl = 8 * g8 + pr, tk = J0 + 8 * ch;
             u32x4_t v = {0u, 0u, 0u, 0u};
-            if (Ii < R && pl < r && tk < Cc) v = *reinterpret_cast<const u32x4_t *>(Qp + (size_t)pl * plane + (size_t)Ii * Cc + tk);
+            if (Ii < R && pl < r && tk < Cc) v = *reinterpret_cast<const u32x4_t *>(Qp + rowb + (size_t)pl * plane + tk);
             qa[g8] = v;
         }
     };
@@ -157,12 +158,13 @@ __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__res
                 }
             }
         }
+        const size_t rowb_out = plane_row_base(I, pg, r, Cc);
 #pragma unroll
         for (int g8 = 0; g8 < KC * 4; ++g8) {
             const int pl = 8 * g8 + pr;
             if (pl < r && J0 + 8 * ch < Cc) {
                 const u32x4_t w = *reinterpret_cast<const u32x4_t *>(slab + pl * ROWB + ((ch ^ swz(pl)) << 4));
-                *reinterpret_cast<u32x4_t *>(P + (size_t)pl * plane + (size_t)I * Cc + J0 + 8 * ch) = w;
+                *reinterpret_cast<u32x4_t *>(P + rowb_out + (size_t)pl * plane + J0 + 8 * ch) = w;
             }
         }
     }
@@ -190,16 +192,17 @@ int encode_outer_blocks(int R, int Cc)
 }
 
 hipError_t launch_encode_outer(const void *A, const void *E, void *P, const void *Qp, float *G, float *part, int R, int Cc,
-                               int r, int accumulate, hipStream_t s)
+                               int r, int accumulate, int pg, hipStream_t s)
 {
+    if (pg <= 0) pg = R;
     const int chunks = (Cc + 63) / 64;
     const int nb = encode_outer_blocks(R, Cc);
     if (r <= 32)
         hipLaunchKernelGGL(encode_outer16_kernel<1>, dim3(nb), dim3(256), 0, s, (const bf16_t *)A, (const bf16_t *)E,
-                           (bf16_t *)P, (const bf16_t *)Qp, part, R, Cc, r, chunks);
+                           (bf16_t *)P, (const bf16_t *)Qp, part, R, Cc, r, chunks, pg);
     else
         hipLaunchKernelGGL(encode_outer16_kernel<2>, dim3(nb), dim3(256), 0, s, (const bf16_t *)A, (const bf16_t *)E,
-                           (bf16_t *)P, (const bf16_t *)Qp, part, R, Cc, r, chunks);
+                           (bf16_t *)P, (const bf16_t *)Qp, part, R, Cc, r, chunks, pg);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_outer_final(part, G, nb, r * 16, accumulate, s);

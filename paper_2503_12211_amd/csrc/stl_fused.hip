@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void stl_block_kernel(const bf16_t *__restrict
                                                         const bf16_t *__restrict__ What, const bf16_t *__restrict__ E,
                                                         const bf16_t *__restrict__ Dm, bf16_t *__restrict__ C,
                                                         bf16_t *__restrict__ Ysave, int M, int K, int N, int r,
-                                                        int blocks_j)
+                                                        int blocks_j, int pg)
 {
     extern __shared__ __align__(16) char smem[];
     // layout: [A-side staging x2][What stage x2]; the exchange buffer reuses everything after the L loop
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256) void stl_block_kernel(const bf16_t *__restrict
 #pragma unroll
         for (int t = 0; t < PW; ++t) {
             const int p = wave * PW + t;
-            srcA[t] = Xin + ((size_t)(p < r ? p : 0) * M + gi) * K + 8 * (lane & 1);
+            srcA[t] = Xin + plane_row_base(gi, pg, r, K) + (size_t)(p < r ? p : 0) * pg * K + 8 * (lane & 1);
         }
     }
     auto issue = [&](int stage) {
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(256) void stl_block_kernel(const bf16_t *__restrict
         for (int q = 0; q < 16; ++q) cq[q] = 0.f;
         for (int p = 0; p < r; ++p) {
             const float y = sY[(p * BI + I) * BJ + J];
-            if (Ysave != nullptr && gi < M && gj < N) Ysave[((size_t)p * M + gi) * N + gj] = f32_to_bf16(y);
+            if (Ysave != nullptr && gi < M && gj < N) Ysave[plane_row_base(gi, pg, r, N) + (size_t)p * pg * N + gj] = f32_to_bf16(y);
 #pragma unroll
             for (int q = 0; q < 16; ++q) cq[q] = fmaf(sD[p * 16 + q], y, cq[q]);
         }
@@ -256,7 +256,7 @@ bool block_forward_eligible(int dtype, int M, int K, int N, int r)
 
 template <int RP, bool ENCODE, bool GELU>
 static hipError_t launch_block_t(const void *Xin, const void *What, const void *E, const void *Dm, void *C, void *Ysave,
-                                 int M, int K, int N, int r, hipStream_t s)
+                                 int M, int K, int N, int r, int pg, hipStream_t s)
 {
     auto kern = fused::stl_block_kernel<RP, ENCODE, GELU>;
     constexpr int smem = fused::smem_bytes<RP, ENCODE>();
@@ -272,28 +272,29 @@ static hipError_t launch_block_t(const void *Xin, const void *What, const void *
     const long total = (long)bi * bj;
     if (total > 0x7fffffffL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(256), smem, s, (const bf16_t *)Xin, (const bf16_t *)What,
-                       (const bf16_t *)E, (const bf16_t *)Dm, (bf16_t *)C, (bf16_t *)Ysave, M, K, N, r, bj);
+                       (const bf16_t *)E, (const bf16_t *)Dm, (bf16_t *)C, (bf16_t *)Ysave, M, K, N, r, bj, pg);
     return hipGetLastError();
 }
 
 template <int RP>
 static hipError_t launch_block_rp(bool encode_in_kernel, const void *Xin, const void *What, const void *E,
-                                  const void *Dm, void *C, void *Ysave, int M, int K, int N, int r, bool gelu,
+                                  const void *Dm, void *C, void *Ysave, int M, int K, int N, int r, bool gelu, int pg,
                                   hipStream_t s)
 {
     if (encode_in_kernel)
-        return gelu ? launch_block_t<RP, true, true>(Xin, What, E, Dm, C, Ysave, M, K, N, r, s)
-                    : launch_block_t<RP, true, false>(Xin, What, E, Dm, C, Ysave, M, K, N, r, s);
-    return gelu ? launch_block_t<RP, false, true>(Xin, What, E, Dm, C, Ysave, M, K, N, r, s)
-                : launch_block_t<RP, false, false>(Xin, What, E, Dm, C, Ysave, M, K, N, r, s);
+        return gelu ? launch_block_t<RP, true, true>(Xin, What, E, Dm, C, Ysave, M, K, N, r, pg, s)
+                    : launch_block_t<RP, true, false>(Xin, What, E, Dm, C, Ysave, M, K, N, r, pg, s);
+    return gelu ? launch_block_t<RP, false, true>(Xin, What, E, Dm, C, Ysave, M, K, N, r, pg, s)
+                : launch_block_t<RP, false, false>(Xin, What, E, Dm, C, Ysave, M, K, N, r, pg, s);
 }
 
 hipError_t launch_block_forward(bool encode_in_kernel, const void *Xin, const void *What, const void *E, const void *Dm,
-                                void *C, void *Ysave, int M, int K, int N, int r, bool gelu, hipStream_t s)
+                                void *C, void *Ysave, int M, int K, int N, int r, bool gelu, int pg, hipStream_t s)
 {
-    if (r <= 8) return launch_block_rp<8>(encode_in_kernel, Xin, What, E, Dm, C, Ysave, M, K, N, r, gelu, s);
-    if (r <= 16) return launch_block_rp<16>(encode_in_kernel, Xin, What, E, Dm, C, Ysave, M, K, N, r, gelu, s);
-    return launch_block_rp<32>(encode_in_kernel, Xin, What, E, Dm, C, Ysave, M, K, N, r, gelu, s);
+    if (pg <= 0) pg = M;
+    if (r <= 8) return launch_block_rp<8>(encode_in_kernel, Xin, What, E, Dm, C, Ysave, M, K, N, r, gelu, pg, s);
+    if (r <= 16) return launch_block_rp<16>(encode_in_kernel, Xin, What, E, Dm, C, Ysave, M, K, N, r, gelu, pg, s);
+    return launch_block_rp<32>(encode_in_kernel, Xin, What, E, Dm, C, Ysave, M, K, N, r, gelu, pg, s);
 }
 
 }  // namespace stl

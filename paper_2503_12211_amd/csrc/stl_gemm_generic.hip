@@ -10,15 +10,14 @@ namespace stl {
 
 template <typename T, typename TO, bool ACC>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const T *__restrict__ A, const T *__restrict__ B,
-                                                           TO *__restrict__ Out, int Mi, int Nj, int Kl, long sa_i,
-                                                           long sa_l, long sb_l, long sb_j)
+                                                           TO *__restrict__ Out, int Mi, int Nj, int Kl, int a_km,
+                                                           int b_km, int a_pg, int b_pg, int o_pg)
 {
     __shared__ float sA[16][64 + 4];
     __shared__ float sB[16][64 + 4];
-    const int p = blockIdx.z;
-    A += (size_t)p * Mi * Kl;
-    B += (size_t)p * Kl * Nj;
-    Out += (size_t)p * Mi * Nj;
+    const int p = blockIdx.z, batch = gridDim.z;
+    // element (row, col) of plane p of an operand stored [row][col] with `ld` columns, rows in groups of pg
+    auto at = [&](int row, int col, int pg, int ld) { return plane_row_base(row, pg, batch, ld) + (size_t)p * pg * ld + col; };
     const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     float acc[4][4];
@@ -31,13 +30,13 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T *__restrict__
         for (int e = threadIdx.x; e < 64 * 16; e += 256) {
             // pick the index that is contiguous in memory as the fast one
             int ii, ll;
-            if (sa_l == 1) { ll = e & 15; ii = e >> 4; } else { ii = e & 63; ll = e >> 6; }
+            if (!a_km) { ll = e & 15; ii = e >> 4; } else { ii = e & 63; ll = e >> 6; }
             const int gi = i0 + ii, gl = l0 + ll;
-            sA[ll][ii] = (gi < Mi && gl < Kl) ? Elem<T>::ld(A + gi * sa_i + gl * sa_l) : 0.f;
+            sA[ll][ii] = (gi < Mi && gl < Kl) ? Elem<T>::ld(A + (a_km ? at(gl, gi, a_pg, Mi) : at(gi, gl, a_pg, Kl))) : 0.f;
             int jj, l2;
-            if (sb_l == 1) { l2 = e & 15; jj = e >> 4; } else { jj = e & 63; l2 = e >> 6; }
+            if (!b_km) { l2 = e & 15; jj = e >> 4; } else { jj = e & 63; l2 = e >> 6; }
             const int gj = j0 + jj, gl2 = l0 + l2;
-            sB[l2][jj] = (gj < Nj && gl2 < Kl) ? Elem<T>::ld(B + gl2 * sb_l + gj * sb_j) : 0.f;
+            sB[l2][jj] = (gj < Nj && gl2 < Kl) ? Elem<T>::ld(B + (b_km ? at(gl2, gj, b_pg, Nj) : at(gj, gl2, b_pg, Kl))) : 0.f;
         }
         __syncthreads();
 #pragma unroll
@@ -58,7 +57,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T *__restrict__
         for (int v = 0; v < 4; ++v) {
             const int gi = i0 + ty * 4 + u, gj = j0 + tx * 4 + v;
             if (gi < Mi && gj < Nj) {
-                TO *o = Out + (size_t)gi * Nj + gj;
+                TO *o = Out + at(gi, gj, o_pg, Nj);
                 if (ACC) Elem<TO>::st(o, Elem<TO>::ld(o) + acc[u][v]);
                 else Elem<TO>::st(o, acc[u][v]);
             }
@@ -69,10 +68,9 @@ template <typename T, typename TO, bool ACC>
 static hipError_t launch_t(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
     dim3 grid((g.Nj + 63) / 64, (g.Mi + 63) / 64, g.batch);
-    const long sa_i = g.a_kmajor ? 1 : g.Kl, sa_l = g.a_kmajor ? g.Mi : 1;
-    const long sb_l = g.b_kmajor ? g.Nj : 1, sb_j = g.b_kmajor ? 1 : g.Kl;
     hipLaunchKernelGGL((gemm_generic_kernel<T, TO, ACC>), grid, dim3(256), 0, s, (const T *)A, (const T *)B, (TO *)Out,
-                       g.Mi, g.Nj, g.Kl, sa_i, sa_l, sb_l, sb_j);
+                       g.Mi, g.Nj, g.Kl, (int)g.a_kmajor, (int)g.b_kmajor, g.a_rows_per_group(), g.b_rows_per_group(),
+                       g.o_rows_per_group());
     return hipGetLastError();
 }
 

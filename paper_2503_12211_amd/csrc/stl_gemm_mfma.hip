@@ -24,13 +24,23 @@ __device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
 // byte offset of the 16-byte chunk c (0..7) of `row` inside one staged operand
 __device__ __forceinline__ int lds_off(int row, int c) { return row * (BK * 2) + ((c ^ swz(row)) << 4); }
 
+// where storage row `row` of plane p of an operand begins (rows in groups of pg, see plane_row_base)
+struct Lay {
+    int pg, batch, p;
+    long ld;
+    __device__ __forceinline__ size_t off(int row) const
+    {
+        return plane_row_base(row, pg, batch, (int)ld) + (size_t)p * pg * ld;
+    }
+};
+
 // ---- HBM -> registers ------------------------------------------------------------------
 // Direct operand: stored [row][l], l contiguous (leading dimension ld elements).
 template <int ROWS, int NT>
 struct DirectLoader {
     static constexpr int CH = ROWS * 8 / NT;  // 16-byte chunks per thread
     u32x4_t v[CH];
-    __device__ __forceinline__ void load(const bf16_t *__restrict__ base, long ld, int row0, int rows_total, int k0,
+    __device__ __forceinline__ void load(const bf16_t *__restrict__ base, const Lay &lay, int row0, int rows_total, int k0,
                                          int Kl, int tid)
     {
 #pragma unroll
@@ -38,7 +48,7 @@ struct DirectLoader {
             const int id = tid + j * NT, row = id >> 3, c = id & 7;
             const int gr = row0 + row, gk = k0 + c * 8;
             u32x4_t z = {0u, 0u, 0u, 0u};
-            if (gr < rows_total && gk < Kl) z = *reinterpret_cast<const u32x4_t *>(base + (size_t)gr * ld + gk);
+            if (gr < rows_total && gk < Kl) z = *reinterpret_cast<const u32x4_t *>(base + lay.off(gr) + gk);
             v[j] = z;
         }
     }
@@ -60,7 +70,7 @@ struct TransLoader {
     static constexpr int RG = ROWS / 8;                // row groups
     static constexpr int UNITS = (BK / 4) * RG / NT;   // units per thread
     u32x4_t v[UNITS][4];
-    __device__ __forceinline__ void load(const bf16_t *__restrict__ base, long ld, int row0, int rows_total, int k0,
+    __device__ __forceinline__ void load(const bf16_t *__restrict__ base, const Lay &lay, int row0, int rows_total, int k0,
                                          int Kl, int tid)
     {
 #pragma unroll
@@ -71,7 +81,7 @@ struct TransLoader {
             for (int kk = 0; kk < 4; ++kk) {
                 const int gk = k0 + kq * 4 + kk;
                 u32x4_t z = {0u, 0u, 0u, 0u};
-                if (gr < rows_total && gk < Kl) z = *reinterpret_cast<const u32x4_t *>(base + (size_t)gk * ld + gr);
+                if (gr < rows_total && gk < Kl) z = *reinterpret_cast<const u32x4_t *>(base + lay.off(gk) + gr);
                 v[u][kk] = z;
             }
         }
@@ -106,7 +116,8 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_T, bool B_T, typename
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(const bf16_t *__restrict__ A,
                                                                           const bf16_t *__restrict__ B,
                                                                           TO *__restrict__ Out, int Mi, int Nj, int Kl,
-                                                                          int tiles_m, int tiles_n, int total)
+                                                                          int tiles_m, int tiles_n, int total, int a_pg,
+                                                                          int b_pg, int o_pg)
 {
     constexpr int NT = WAVES_M * WAVES_N * 64;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -122,10 +133,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(const 
     const int rem = bid - p * per_plane;
     const int i0 = (rem / tiles_n) * BM, j0 = (rem % tiles_n) * BN;
 
-    A += (size_t)p * Mi * Kl;
-    B += (size_t)p * Kl * Nj;
-    Out += (size_t)p * Mi * Nj;
-    const long lda = A_T ? Mi : Kl, ldb = B_T ? Nj : Kl;
+    const int batch = total / per_plane;
+    const Lay lda{a_pg, batch, p, A_T ? Mi : Kl}, ldb{b_pg, batch, p, B_T ? Nj : Kl}, ldo{o_pg, batch, p, Nj};
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -208,7 +217,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(const 
             const int gi = gi_base + rr;
             if (gi < Mi && gj < Nj) {
                 u32x4_t w = *reinterpret_cast<const u32x4_t *>(slab + rr * PITCH + (lane % LPR) * 16);
-                TO *o = Out + (size_t)gi * Nj + gj;
+                TO *o = Out + ldo.off(gi) + gj;
                 if (ACC) {
                     const f32x4_t old = *reinterpret_cast<const f32x4_t *>(o);
                     f32x4_t nw = __builtin_bit_cast(f32x4_t, w);
@@ -251,7 +260,8 @@ static hipError_t launch_cfg(const GemmDesc &g, const void *A, const void *B, vo
     const long total = (long)tiles_m * tiles_n * g.batch;
     if (total > 0x7fffffffL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), smem, s, (const bf16_t *)A,
-                       (const bf16_t *)B, (TO *)Out, g.Mi, g.Nj, g.Kl, tiles_m, tiles_n, (int)total);
+                       (const bf16_t *)B, (TO *)Out, g.Mi, g.Nj, g.Kl, tiles_m, tiles_n, (int)total, g.a_rows_per_group(),
+                       g.b_rows_per_group(), g.o_rows_per_group());
     return hipGetLastError();
 }
 

@@ -53,9 +53,17 @@ struct Src {
     static constexpr int NI = ROWS / 16 / NW;          // instructions per wavefront
     static constexpr int CPR = ROWS / 8;               // 16-byte chunks per LDS row of the [l][row] form
     const bf16_t *p[NI];
-    long step;  // elements to advance per stage
-    __device__ __forceinline__ void init(const bf16_t *base, long ld, int row0, int rows_total, int wave, int lane)
+    long step;   // elements to advance per stage
+    long jump;   // [l][row] form: extra elements when the next stage starts a new group of stored rows
+    int kpos, pg;
+    // base: the whole batched operand; plane p of `batch`; stored rows come in groups of pg (see plane_row_base), and a
+    // stage's 32 stored rows of the [l][row] form never straddle two groups (pg % 32 == 0)
+    __device__ __forceinline__ void init(const bf16_t *base, long ld, int row0, int rows_total, int wave, int lane, int plane,
+                                         int batch, int pg_)
     {
+        pg = pg_;
+        kpos = 0;
+        const size_t poff = (size_t)plane * pg * ld;
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const int q = NI * wave + j;
@@ -63,29 +71,41 @@ struct Src {
                 const int row = 16 * q + (lane >> 2), c = (lane & 3) ^ fswz<SWZ>(row);
                 int gr = row0 + row;
                 gr = gr < rows_total ? gr : rows_total - 1;   // rows past the edge feed only discarded outputs
-                p[j] = base + (size_t)gr * ld + 8 * c;
+                p[j] = base + plane_row_base(gr, pg, batch, (int)ld) + poff + 8 * c;
             } else {
                 const int k = (64 / CPR) * q + lane / CPR, nc = (lane % CPR) ^ gswz(k);
                 int gc = row0 + 8 * nc;
                 gc = gc < rows_total ? gc : rows_total - 8;
-                p[j] = base + (size_t)k * ld + gc;
+                p[j] = base + plane_row_base(k, pg, batch, (int)ld) + poff + gc;
             }
         }
         step = KMAJOR ? (long)BKS * ld : BKS;
+        jump = KMAJOR ? (long)(batch - 1) * pg * ld : 0;
     }
     // instruction j of this wavefront's share (the main loop spreads them between MFMAs)
     __device__ __forceinline__ void issue_one(uint32_t oper_stage, int wave, int j)
     {
         dma16(p[j], oper_stage + (NI * wave + j) * 1024);
-        p[j] += step;
+    }
+    // after the last instruction of a stage: point at the next stage
+    __device__ __forceinline__ void next_stage()
+    {
+        long adv = step;
+        if (KMAJOR) {
+            kpos += BKS;
+            if (kpos == pg) {
+                kpos = 0;
+                adv += jump;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NI; ++j) p[j] += adv;
     }
     __device__ __forceinline__ void issue(uint32_t oper_stage, int wave)   // LDS byte address of the operand stage
     {
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            dma16(p[j], oper_stage + (NI * wave + j) * 1024);
-            p[j] += step;
-        }
+        for (int j = 0; j < NI; ++j) dma16(p[j], oper_stage + (NI * wave + j) * 1024);
+        next_stage();
     }
 };
 
@@ -216,7 +236,7 @@ __device__ unsigned long long g_timeline[8192 * 4];
 template <int WAVES_M, int WAVES_N, int NS, int SWZ, bool A_T, bool B_T, typename TO, bool ACC>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B,
                                                         TO *__restrict__ Out, int Mi, int Nj, int Kl, int tiles_m,
-                                                        int tiles_n, int total, int dbg_arg)
+                                                        int tiles_n, int total, int dbg_arg, int a_pg, int b_pg, int o_pg)
 {
     // Timing-only ablation switches (they skip parts of the kernel and give wrong results): compiled in only with
     // -DSTL_GEMM_ABLATE; in the normal build dbg is the constant 0 and every test below folds away.
@@ -242,6 +262,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int per_plane = tiles_m * tiles_n;
+    const int batch = total / per_plane;
     const int nks = Kl / BKS;
     const uint32_t smem_lds = (uint32_t)(uintptr_t)STL_LDS(smem);
 
@@ -266,8 +287,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
     auto start_block = [&](int v) {      // point the DMA sources at block v and put its first NS-1 stages in flight
         int p, i0, j0;
         locate(v, p, i0, j0);
-        sa.init(A + (size_t)p * Mi * Kl, A_T ? Mi : Kl, i0, Mi, wave, lane);
-        sb.init(B + (size_t)p * Kl * Nj, B_T ? Nj : Kl, j0, Nj, wave, lane);
+        sa.init(A, A_T ? Mi : Kl, i0, Mi, wave, lane, p, batch, a_pg);
+        sb.init(B, B_T ? Nj : Kl, j0, Nj, wave, lane, p, batch, b_pg);
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s) {
             if (s < nks) {
@@ -364,6 +385,12 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
             // s+1 -- after the last stage that reads a stale ring slot whose values are never used; refill B)
             step(std::integral_constant<int, 0>{}, cur, 1, std::true_type{});
             step(std::integral_constant<int, 1>{}, nxt, 0, std::false_type{});
+            if constexpr (REFILL) {
+                if (refill) {
+                    sa.next_stage();
+                    sb.next_stage();
+                }
+            }
         };
         const int n_refill = nks > NS - 1 ? nks - (NS - 1) : 0;
         for (int s = 0; s < n_refill; ++s) stage(s, std::true_type{});
@@ -376,7 +403,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
 
         // Epilogue.  With operands passed as (B fragment, A fragment) accumulator e of fragment (a, b) is
         //   Out[row = 32a + lane%32][column = 32b + 8*(e/4) + 4*(lane/32) + e%4].
-        TO *outp = Out + (size_t)p * Mi * Nj;
+        // output rows of one pass lie in one group of the output layout (groups are multiples of 32 rows, or everything)
+        TO *outp = Out + (size_t)p * o_pg * Nj;
         const int frow = lane & 31, fhalf = lane >> 5;
         constexpr int LPR = WN * ES / 16;                   // lanes per row in the store phase
         constexpr int RPI = 64 / LPR;                       // rows per store instruction
@@ -406,6 +434,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
                 // same wavefront wrote the slab; LDS operations of a wavefront complete in order
                 asm volatile("" ::: "memory");
                 const int gi_base = i0 + wm * WM + a * 32 + pass * RP;
+                const size_t row_off = plane_row_base(gi_base < Mi ? gi_base : 0, o_pg, batch, Nj);
                 const int gj = j0 + wn * WN + (lane % LPR) * (16 / ES);
 #pragma unroll
                 for (int it = 0; it < RP / RPI; ++it) {
@@ -413,7 +442,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
                     const int gi = gi_base + rr;
                     const u32x4_t w = *reinterpret_cast<const u32x4_t *>(slab + rr * PITCH + (lane % LPR) * 16);
                     if (gi < Mi && gj < Nj && !(dbg & 1)) {
-                        TO *o = outp + (size_t)gi * Nj + gj;
+                        TO *o = outp + row_off + (size_t)rr * Nj + gj;
                         if (ACC) {
                             const f32x4_t old = *reinterpret_cast<const f32x4_t *>(o);
                             f32x4_t nw = __builtin_bit_cast(f32x4_t, w);
@@ -442,6 +471,10 @@ bool plane_gemm_pipe_eligible(const GemmDesc &g)
 {
     if (!plane_gemm_mfma_eligible(g)) return false;
     if (g.Kl % pipe::BKS) return false;
+    // a stage's 32 stored rows of an [l][row] operand stay inside one group; so do the rows of an epilogue pass
+    if (g.a_kmajor && g.a_rows_per_group() % pipe::BKS) return false;
+    if (g.b_kmajor && g.b_rows_per_group() % pipe::BKS) return false;
+    if (g.o_pg > 0 && g.o_pg % 32) return false;
     // a clamped edge chunk must still lie inside the operand
     if (g.Mi < 8 || g.Nj < 8) return false;
     return g.Mi > 128 && g.Nj > 128;
@@ -490,7 +523,7 @@ static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *
     const int dbg = 0;
 #endif
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), smem, s, (const bf16_t *)A, (const bf16_t *)B, (TO *)Out, g.Mi, g.Nj,
-                       g.Kl, tiles_m, tiles_n, (int)total, dbg);
+                       g.Kl, tiles_m, tiles_n, (int)total, dbg, g.a_rows_per_group(), g.b_rows_per_group(), g.o_rows_per_group());
     return hipGetLastError();
 }
 

@@ -6,24 +6,26 @@
 namespace stl {
 
 // dtype: 0 = fp32 storage, 1 = bf16 storage (matches stl_dtype_t)
+// pg: rows per group of the plane tensor's layout (see plane_row_base); 0 = plane-major (one group of all rows)
+constexpr int kPlaneGroup = 64;   // group size of the activation-side plane tensors
 
 // planes P[p][R][Cc] <- encoder E (r x 16) applied to every 4x4 tile of A (4R x 4Cc)
-hipError_t launch_encode(int dtype, const void *A, const void *E, void *P, int R, int Cc, int r, hipStream_t s);
+hipError_t launch_encode(int dtype, const void *A, const void *E, void *P, int R, int Cc, int r, int pg, hipStream_t s);
 // matrix Cmat (4R x 4Cc) <- decoder Dm^T (r x 16 stored) applied to planes P[p][R][Cc]
-hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, int R, int Cc, int r, bool gelu,
+hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, int R, int Cc, int r, bool gelu, int pg,
                          hipStream_t s);
 
 // G[p][q] (+)= sum_tiles P[p][tile] * tileview(V)[tile][q]; `part` holds outer_reduce_blocks(R*Cc) * r * 16 floats
 int outer_reduce_blocks(int64_t tiles);
 hipError_t launch_outer_reduce(int dtype, const void *P, const void *V, float *G, float *part, int R, int Cc, int r,
-                               int accumulate, hipStream_t s);
+                               int accumulate, int pg, hipStream_t s);
 
 // decode and basis gradient in one pass over the planes (bf16): Cmat <- decode(P, Dm), G (+)= P . tileview(V);
 // `part` holds decode_outer_blocks(R, Cc) * r * 16 floats
 bool decode_outer_eligible(int dtype, int Cc);
 int decode_outer_blocks(int R, int Cc);
 hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const void *V, float *G, float *part, int R,
-                               int Cc, int r, int accumulate, hipStream_t s);
+                               int Cc, int r, int accumulate, int pg, hipStream_t s);
 
 // G[i] (+)= sum over nb partials part[b][i], i < n_out, in block order (second stage of the basis-gradient sums)
 hipError_t launch_outer_final(const float *part, float *G, int nb, int n_out, int accumulate, hipStream_t s);
@@ -33,7 +35,7 @@ hipError_t launch_outer_final(const float *part, float *G, int nb, int n_out, in
 bool encode_outer_eligible(int dtype, int Cc);
 int encode_outer_blocks(int R, int Cc);
 hipError_t launch_encode_outer(const void *A, const void *E, void *P, const void *Qp, float *G, float *part, int R, int Cc,
-                               int r, int accumulate, hipStream_t s);
+                               int r, int accumulate, int pg, hipStream_t s);
 
 // out[i] = bf16(in[i]), round to nearest even
 hipError_t launch_cast_bf16(const float *in, void *out, size_t n, hipStream_t s);
@@ -42,7 +44,7 @@ hipError_t launch_cast_bf16(const float *in, void *out, size_t n, hipStream_t s)
 // r1 x R x Cc -> planes Q r2 x R x Cc, the hidden activation never stored
 bool recode_eligible(int dtype, int Cc);
 hipError_t launch_recode(const void *P, const void *Dm, const void *E2, void *Q, int R, int Cc, int r1, int r2, bool gelu,
-                         hipStream_t s);
+                         int pg, hipStream_t s);
 
 // Batched plane products  Out[p][i][j] (+)= sum_l A[p](i,l) * B[p](l,j),  p < batch, dense planes.
 struct GemmDesc {
@@ -52,6 +54,12 @@ struct GemmDesc {
     bool b_kmajor;    // true:  B[p] stored [l][j] (j contiguous);  false: stored [j][l] (l contiguous)
     bool out_f32;     // output stored as fp32 regardless of dtype (weight gradient)
     bool accumulate;  // Out += result (only with out_f32)
+    // layout of each operand: rows per group (see plane_row_base), counted in the operand's stored rows -- i for A
+    // stored [i][l], l for A stored [l][i], and so on; 0 = plane-major
+    int a_pg = 0, b_pg = 0, o_pg = 0;
+    int a_rows_per_group() const { return a_pg > 0 ? a_pg : (a_kmajor ? Kl : Mi); }
+    int b_rows_per_group() const { return b_pg > 0 ? b_pg : (b_kmajor ? Kl : Nj); }
+    int o_rows_per_group() const { return o_pg > 0 ? o_pg : Mi; }
 };
 hipError_t launch_plane_gemm(int dtype, const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s);
 // the slow any-shape path, also used directly for fp32 storage
@@ -68,6 +76,6 @@ hipError_t launch_plane_gemm_pipe(const GemmDesc &g, const void *A, const void *
 // (single-launch fused form); otherwise Xin is Xhat.  Ysave may be NULL.  bf16 storage only.
 bool block_forward_eligible(int dtype, int M, int K, int N, int r);
 hipError_t launch_block_forward(bool encode_in_kernel, const void *Xin, const void *What, const void *E, const void *Dm,
-                                void *C, void *Ysave, int M, int K, int N, int r, bool gelu, hipStream_t s);
+                                void *C, void *Ysave, int M, int K, int N, int r, bool gelu, int pg, hipStream_t s);
 
 }  // namespace stl

@@ -22,7 +22,7 @@ typedef short v4i16_t __attribute__((ext_vector_type(4)));
 template <bool GELU, int KC>   // KC = number of 32-plane groups of the larger of the two ranks (1: <= 32, 2: <= 64)
 __global__ __launch_bounds__(256) void recode_mfma_kernel(const bf16_t *__restrict__ P, const bf16_t *__restrict__ Dm,
                                                           const bf16_t *__restrict__ E2, bf16_t *__restrict__ Q, int R,
-                                                          int Cc, int r1, int r2, int chunks)
+                                                          int Cc, int r1, int r2, int chunks, int pg)
 {
     constexpr int ROWB = 128;                               // bytes per LDS row (64 tiles)
     __shared__ __align__(16) char slab_all[4][KC * 32 * ROWB];
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void recode_mfma_kernel(const bf16_t *__restri
     // the row already alternates the bank half (128-byte rows); the other three bits shift the chunk index.
     auto swz = [](int row) { return ((row >> 1) & 1) | (((row >> 3) & 3) << 1); };
 
-    const size_t plane = (size_t)R * Cc;
+    const size_t plane = (size_t)pg * Cc;
     const long items = (long)R * chunks;
     // (tile row, chunk) of this wavefront's item, advanced without a division per round
     const long stride = (long)gridDim.x * 4;
@@ -71,11 +71,12 @@ __global__ __launch_bounds__(256) void recode_mfma_kernel(const bf16_t *__restri
     u32x4_t pre[KC * 4];
     auto fetch = [&](int Ii, int cki) {
         const int Jl = cki * 64 + 8 * ch;
+        const size_t rowb = Ii < R ? plane_row_base(Ii, pg, r1, Cc) : 0;
 #pragma unroll
         for (int g8 = 0; g8 < KC * 4; ++g8) {
             const int pl = 8 * g8 + pr;
             u32x4_t v = {0u, 0u, 0u, 0u};
-            if (Ii < R && pl < r1 && Jl < Cc) v = *reinterpret_cast<const u32x4_t *>(P + (size_t)pl * plane + (size_t)Ii * Cc + Jl);
+            if (Ii < R && pl < r1 && Jl < Cc) v = *reinterpret_cast<const u32x4_t *>(P + rowb + (size_t)pl * plane + Jl);
             pre[g8] = v;
         }
     };
@@ -148,12 +149,13 @@ __global__ __launch_bounds__(256) void recode_mfma_kernel(const bf16_t *__restri
                 }
             }
         }
+        const size_t rowb_out = plane_row_base(I, pg, r2, Cc);
 #pragma unroll
         for (int g8 = 0; g8 < KC * 4; ++g8) {
             const int pl = 8 * g8 + pr;
             if (pl < r2 && J0 + 8 * ch < Cc) {
                 const u32x4_t w = *reinterpret_cast<const u32x4_t *>(slab + pl * ROWB + ((ch ^ swo(pl)) << 4));
-                *reinterpret_cast<u32x4_t *>(Q + (size_t)pl * plane + (size_t)I * Cc + J0 + 8 * ch) = w;
+                *reinterpret_cast<u32x4_t *>(Q + rowb_out + (size_t)pl * plane + J0 + 8 * ch) = w;
             }
         }
     }
@@ -162,8 +164,9 @@ __global__ __launch_bounds__(256) void recode_mfma_kernel(const bf16_t *__restri
 bool recode_eligible(int dtype, int Cc) { return dtype == 1 && (Cc % 8) == 0; }
 
 hipError_t launch_recode(const void *P, const void *Dm, const void *E2, void *Q, int R, int Cc, int r1, int r2, bool gelu,
-                         hipStream_t s)
+                         int pg, hipStream_t s)
 {
+    if (pg <= 0) pg = R;
     const int chunks = (Cc + 63) / 64;
     const long items = (long)R * chunks;
     long blocks = (items + 3) / 4;
@@ -172,11 +175,11 @@ hipError_t launch_recode(const void *P, const void *Dm, const void *E2, void *Q,
     const bf16_t *p = (const bf16_t *)P, *d = (const bf16_t *)Dm, *e = (const bf16_t *)E2;
     bf16_t *q = (bf16_t *)Q;
     if (r1 <= 32 && r2 <= 32) {
-        if (gelu) hipLaunchKernelGGL((recode_mfma_kernel<true, 1>), grid, block, 0, s, p, d, e, q, R, Cc, r1, r2, chunks);
-        else hipLaunchKernelGGL((recode_mfma_kernel<false, 1>), grid, block, 0, s, p, d, e, q, R, Cc, r1, r2, chunks);
+        if (gelu) hipLaunchKernelGGL((recode_mfma_kernel<true, 1>), grid, block, 0, s, p, d, e, q, R, Cc, r1, r2, chunks, pg);
+        else hipLaunchKernelGGL((recode_mfma_kernel<false, 1>), grid, block, 0, s, p, d, e, q, R, Cc, r1, r2, chunks, pg);
     } else {
-        if (gelu) hipLaunchKernelGGL((recode_mfma_kernel<true, 2>), grid, block, 0, s, p, d, e, q, R, Cc, r1, r2, chunks);
-        else hipLaunchKernelGGL((recode_mfma_kernel<false, 2>), grid, block, 0, s, p, d, e, q, R, Cc, r1, r2, chunks);
+        if (gelu) hipLaunchKernelGGL((recode_mfma_kernel<true, 2>), grid, block, 0, s, p, d, e, q, R, Cc, r1, r2, chunks, pg);
+        else hipLaunchKernelGGL((recode_mfma_kernel<false, 2>), grid, block, 0, s, p, d, e, q, R, Cc, r1, r2, chunks, pg);
     }
     return hipGetLastError();
 }

@@ -13,7 +13,7 @@ namespace stl {
 // ---------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void encode_kernel(const T *__restrict__ A, const T *__restrict__ E,
-                                                     T *__restrict__ P, int R, int Cc, int r)
+                                                     T *__restrict__ P, int R, int Cc, int r, int pg)
 {
     __shared__ float sE[64 * 16];
     const int tid = threadIdx.y * blockDim.x + threadIdx.x;
@@ -31,8 +31,8 @@ __global__ __launch_bounds__(256) void encode_kernel(const T *__restrict__ A, co
 #pragma unroll
         for (int b = 0; b < 4; ++b) x[a * 4 + b] = Elem<T>::ld(A + ((size_t)I * 4 + a) * ld + (size_t)L * 4 + b);
 
-    const size_t plane = (size_t)R * Cc;
-    T *out = P + (size_t)I * Cc + L;
+    const size_t plane = (size_t)pg * Cc;
+    T *out = P + plane_row_base(I, pg, r, Cc) + L;
     for (int p = 0; p < r; ++p) {
         float s = 0.f;
 #pragma unroll
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const T *__restrict__ A, co
 // ---------------------------------------------------------------------------------------
 template <typename T, bool GELU>
 __global__ __launch_bounds__(256) void decode_kernel(const T *__restrict__ P, const T *__restrict__ Dm,
-                                                     T *__restrict__ Cmat, int R, int Cc, int r)
+                                                     T *__restrict__ Cmat, int R, int Cc, int r, int pg)
 {
     __shared__ float sD[64 * 16];
     const int tid = threadIdx.y * blockDim.x + threadIdx.x;
@@ -57,8 +57,8 @@ __global__ __launch_bounds__(256) void decode_kernel(const T *__restrict__ P, co
     const int I = blockIdx.y * blockDim.y + threadIdx.y;
     if (J >= Cc || I >= R) return;
 
-    const size_t plane = (size_t)R * Cc;
-    const T *in = P + (size_t)I * Cc + J;
+    const size_t plane = (size_t)pg * Cc;
+    const T *in = P + plane_row_base(I, pg, r, Cc) + J;
     float c[16];
 #pragma unroll
     for (int q = 0; q < 16; ++q) c[q] = 0.f;
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const T *__restrict__ P, co
 template <typename T>
 __global__ __launch_bounds__(256) void outer_partial_kernel(const T *__restrict__ P, const T *__restrict__ V,
                                                             float *__restrict__ part, int R, int Cc, int r,
-                                                            int tiles_per_block)
+                                                            int tiles_per_block, int pg)
 {
     // 256 threads: q = tid & 15, tile lane = tid >> 4 (16 tiles in flight); loop over planes.
     __shared__ float red[16][16];
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256) void outer_partial_kernel(const T *__restrict_
         for (size_t tile = t0 + tl; tile < t1; tile += 16) {
             const size_t I = tile / Cc, J = tile % Cc;
             const float v = Elem<T>::ld(V + (I * 4 + (q >> 2)) * ld + J * 4 + (q & 3));
-            const float y = Elem<T>::ld(P + (size_t)p * T_total + tile);
+            const float y = Elem<T>::ld(P + plane_row_base((int)I, pg, r, Cc) + (size_t)p * pg * Cc + J);
             s = fmaf(y, v, s);
         }
         red[tl][q] = s;
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void outer_final_kernel(const float *__restric
 // holds 4 consecutive tiles of a plane and writes them with one 8-byte store.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void encode_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ E,
-                                                          bf16_t *__restrict__ P, int R, int Cc, int r, int chunks)
+                                                          bf16_t *__restrict__ P, int R, int Cc, int r, int chunks, int pg)
 {
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long item = (long)blockIdx.x * 4 + wave;          // (tile row, chunk of 128 tile columns)
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(const bf16_t *__restri
             row[a][c] = z;
         }
 
-    const size_t plane = (size_t)R * Cc;
+    const size_t plane = (size_t)pg * Cc, rowb = plane_row_base(I, pg, r, Cc);
     for (int g = 0; g < r; g += 32) {
         const int pl = g + j;
         u32x4_t ev = {0u, 0u, 0u, 0u};
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(const bf16_t *__restri
                 const int po = g + 8 * (v >> 2) + 4 * h + (v & 3);
                 if (po < r) {
                     u32x2_t w = {pack_bf16x2(acc[0][v], acc[1][v]), pack_bf16x2(acc[2][v], acc[3][v])};
-                    *reinterpret_cast<u32x2_t *>(P + (size_t)po * plane + (size_t)I * Cc + Jl) = w;
+                    *reinterpret_cast<u32x2_t *>(P + rowb + (size_t)po * plane + Jl) = w;
                 }
             }
         }
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(const bf16_t *__restri
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restrict__ P, const bf16_t *__restrict__ V,
                                                          float *__restrict__ part, int R, int Cc, int r,
-                                                         int tiles_per_block)
+                                                         int tiles_per_block, int pg)
 {
     constexpr int PITCH = 64 + 8;                       // bf16 elements per LDS row (16-byte aligned rows)
     __shared__ __align__(16) bf16_t sV[4][16][PITCH];
@@ -243,12 +243,14 @@ __global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restric
         }
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            const long tk = tb + 32 * s + 8 * kq;        // 8 consecutive tiles; all inside or all outside (T % 8 == 0)
+            const long tk = tb + 32 * s + 8 * kq;        // 8 consecutive tiles of one tile row (Cc % 8 == 0): all in or all out
+            const int Ik = (int)(tk / Cc);
+            const size_t off = tk < t1 ? plane_row_base(Ik, pg, r, Cc) + (size_t)(tk - (long)Ik * Cc) : 0;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int pl = 16 * g + q;
                 u32x4_t av = {0u, 0u, 0u, 0u};
-                if (g < ngroups && pl < r && tk < t1) av = *reinterpret_cast<const u32x4_t *>(P + (size_t)pl * T + tk);
+                if (g < ngroups && pl < r && tk < t1) av = *reinterpret_cast<const u32x4_t *>(P + off + (size_t)pl * pg * Cc);
                 pa[s][g] = av;
             }
         }
@@ -306,7 +308,7 @@ typedef short v4i16_t __attribute__((ext_vector_type(4)));
 template <bool GELU, int KC, bool OUTER>   // KC = number of 32-plane groups (1: r <= 32, 2: r <= 64)
 __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restrict__ P, const bf16_t *__restrict__ Dm,
                                                           bf16_t *__restrict__ Cmat, int R, int Cc, int r, int chunks,
-                                                          const bf16_t *__restrict__ V, float *__restrict__ part)
+                                                          const bf16_t *__restrict__ V, float *__restrict__ part, int pg)
 {
     constexpr int ROWB = 128;                               // bytes per LDS row (64 tiles)
     constexpr int VPITCH = 64 + 8;                          // bf16 elements per row of the entry x tile staging
@@ -337,7 +339,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
     // (planes 0-3 and 8-11, or 4-7 and 12-15, of a 16-tile column group) fall into different bank windows
     auto swz = [](int row) { return ((((row >> 1) & 1) | (((row >> 3) & 1) << 1)) << 1); };
 
-    const size_t plane = (size_t)R * Cc;
+    const size_t plane = (size_t)pg * Cc;
     const size_t ld = (size_t)Cc * 4;
     const long items = (long)R * chunks;
     // (tile row, chunk) of this wavefront's item, advanced without a division per round
@@ -353,11 +355,12 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
     u32x2_t xpre[OUTER ? 4 : 1];
     auto fetch = [&](int Ii, int cki) {
         const int Jl = cki * 64 + 8 * ch;
+        const size_t rowb = Ii < R ? plane_row_base(Ii, pg, r, Cc) : 0;
 #pragma unroll
         for (int g8 = 0; g8 < KC * 4; ++g8) {
             const int pl = 8 * g8 + pr;
             u32x4_t v = {0u, 0u, 0u, 0u};       // planes >= r stay zero (they meet zero D entries, but must be finite)
-            if (Ii < R && pl < r && Jl < Cc) v = *reinterpret_cast<const u32x4_t *>(P + (size_t)pl * plane + (size_t)Ii * Cc + Jl);
+            if (Ii < R && pl < r && Jl < Cc) v = *reinterpret_cast<const u32x4_t *>(P + rowb + (size_t)pl * plane + Jl);
             pre[g8] = v;
         }
         if (OUTER) {
@@ -483,40 +486,42 @@ hipError_t launch_cast_bf16(const float *in, void *out, size_t n, hipStream_t s)
 }
 
 template <typename T>
-static hipError_t launch_encode_t(const void *A, const void *E, void *P, int R, int Cc, int r, hipStream_t s)
+static hipError_t launch_encode_t(const void *A, const void *E, void *P, int R, int Cc, int r, int pg, hipStream_t s)
 {
     dim3 block(64, 4), grid((Cc + 63) / 64, (R + 3) / 4);
-    hipLaunchKernelGGL(encode_kernel<T>, grid, block, 0, s, (const T *)A, (const T *)E, (T *)P, R, Cc, r);
+    hipLaunchKernelGGL(encode_kernel<T>, grid, block, 0, s, (const T *)A, (const T *)E, (T *)P, R, Cc, r, pg);
     return hipGetLastError();
 }
 
-hipError_t launch_encode(int dtype, const void *A, const void *E, void *P, int R, int Cc, int r, hipStream_t s)
+hipError_t launch_encode(int dtype, const void *A, const void *E, void *P, int R, int Cc, int r, int pg, hipStream_t s)
 {
+    if (pg <= 0) pg = R;
     if (dtype == 1 && (Cc % 4) == 0) {
         const int chunks = (Cc + 127) / 128;
         const long items = (long)R * chunks;
         hipLaunchKernelGGL(encode_mfma_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, (const bf16_t *)A,
-                           (const bf16_t *)E, (bf16_t *)P, R, Cc, r, chunks);
+                           (const bf16_t *)E, (bf16_t *)P, R, Cc, r, chunks, pg);
         return hipGetLastError();
     }
-    return dtype == 0 ? launch_encode_t<float>(A, E, P, R, Cc, r, s) : launch_encode_t<bf16_t>(A, E, P, R, Cc, r, s);
+    return dtype == 0 ? launch_encode_t<float>(A, E, P, R, Cc, r, pg, s) : launch_encode_t<bf16_t>(A, E, P, R, Cc, r, pg, s);
 }
 
 template <typename T>
-static hipError_t launch_decode_t(const void *P, const void *Dm, void *Cmat, int R, int Cc, int r, bool gelu,
+static hipError_t launch_decode_t(const void *P, const void *Dm, void *Cmat, int R, int Cc, int r, bool gelu, int pg,
                                   hipStream_t s)
 {
     dim3 block(64, 4), grid((Cc + 63) / 64, (R + 3) / 4);
     if (gelu)
-        hipLaunchKernelGGL((decode_kernel<T, true>), grid, block, 0, s, (const T *)P, (const T *)Dm, (T *)Cmat, R, Cc, r);
+        hipLaunchKernelGGL((decode_kernel<T, true>), grid, block, 0, s, (const T *)P, (const T *)Dm, (T *)Cmat, R, Cc, r, pg);
     else
-        hipLaunchKernelGGL((decode_kernel<T, false>), grid, block, 0, s, (const T *)P, (const T *)Dm, (T *)Cmat, R, Cc, r);
+        hipLaunchKernelGGL((decode_kernel<T, false>), grid, block, 0, s, (const T *)P, (const T *)Dm, (T *)Cmat, R, Cc, r, pg);
     return hipGetLastError();
 }
 
-hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, int R, int Cc, int r, bool gelu,
+hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, int R, int Cc, int r, bool gelu, int pg,
                          hipStream_t s)
 {
+    if (pg <= 0) pg = R;
     if (dtype == 1 && (Cc % 8) == 0) {
         const int chunks = (Cc + 63) / 64;
         const long items = (long)R * chunks;
@@ -526,16 +531,16 @@ hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, i
         const bf16_t *p = (const bf16_t *)P, *d = (const bf16_t *)Dm;
         bf16_t *c = (bf16_t *)Cmat;
         if (r <= 32) {
-            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 1, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr);
-            else hipLaunchKernelGGL((decode_mfma_kernel<false, 1, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr);
+            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 1, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr, pg);
+            else hipLaunchKernelGGL((decode_mfma_kernel<false, 1, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr, pg);
         } else {
-            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 2, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr);
-            else hipLaunchKernelGGL((decode_mfma_kernel<false, 2, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr);
+            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 2, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr, pg);
+            else hipLaunchKernelGGL((decode_mfma_kernel<false, 2, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr, pg);
         }
         return hipGetLastError();
     }
-    return dtype == 0 ? launch_decode_t<float>(P, Dm, Cmat, R, Cc, r, gelu, s)
-                      : launch_decode_t<bf16_t>(P, Dm, Cmat, R, Cc, r, gelu, s);
+    return dtype == 0 ? launch_decode_t<float>(P, Dm, Cmat, R, Cc, r, gelu, pg, s)
+                      : launch_decode_t<bf16_t>(P, Dm, Cmat, R, Cc, r, gelu, pg, s);
 }
 
 hipError_t launch_outer_final(const float *part, float *G, int nb, int n_out, int accumulate, hipStream_t s)
@@ -554,16 +559,17 @@ int decode_outer_blocks(int R, int Cc)
 }
 
 hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const void *V, float *G, float *part, int R,
-                               int Cc, int r, int accumulate, hipStream_t s)
+                               int Cc, int r, int accumulate, int pg, hipStream_t s)
 {
+    if (pg <= 0) pg = R;
     const int chunks = (Cc + 63) / 64;
     const int nb = decode_outer_blocks(R, Cc);
     const bf16_t *p = (const bf16_t *)P, *d = (const bf16_t *)Dm, *v = (const bf16_t *)V;
     bf16_t *c = (bf16_t *)Cmat;
     if (r <= 32)
-        hipLaunchKernelGGL((decode_mfma_kernel<false, 1, true>), dim3(nb), dim3(256), 0, s, p, d, c, R, Cc, r, chunks, v, part);
+        hipLaunchKernelGGL((decode_mfma_kernel<false, 1, true>), dim3(nb), dim3(256), 0, s, p, d, c, R, Cc, r, chunks, v, part, pg);
     else
-        hipLaunchKernelGGL((decode_mfma_kernel<false, 2, true>), dim3(nb), dim3(256), 0, s, p, d, c, R, Cc, r, chunks, v, part);
+        hipLaunchKernelGGL((decode_mfma_kernel<false, 2, true>), dim3(nb), dim3(256), 0, s, p, d, c, R, Cc, r, chunks, v, part, pg);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int n_out = r * 16;
@@ -586,20 +592,21 @@ int outer_reduce_blocks(int64_t tiles)
 }
 
 hipError_t launch_outer_reduce(int dtype, const void *P, const void *V, float *G, float *part, int R, int Cc, int r,
-                               int accumulate, hipStream_t s)
+                               int accumulate, int pg, hipStream_t s)
 {
+    if (pg <= 0) pg = R;
     const int64_t tiles = (int64_t)R * Cc;
     const int tpb = outer_tiles_per_block(tiles);
     const int nb = outer_reduce_blocks(tiles);
     if (dtype == 0)
         hipLaunchKernelGGL(outer_partial_kernel<float>, dim3(nb), dim3(256), 0, s, (const float *)P, (const float *)V,
-                           part, R, Cc, r, tpb);
-    else if (tiles % 8 == 0)
+                           part, R, Cc, r, tpb, pg);
+    else if (Cc % 8 == 0)
         hipLaunchKernelGGL(outer_mfma_kernel, dim3(nb), dim3(256), 0, s, (const bf16_t *)P, (const bf16_t *)V, part, R,
-                           Cc, r, tpb);
+                           Cc, r, tpb, pg);
     else
         hipLaunchKernelGGL(outer_partial_kernel<bf16_t>, dim3(nb), dim3(256), 0, s, (const bf16_t *)P,
-                           (const bf16_t *)V, part, R, Cc, r, tpb);
+                           (const bf16_t *)V, part, R, Cc, r, tpb, pg);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int n_out = r * 16;

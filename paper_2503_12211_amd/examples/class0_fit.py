@@ -70,8 +70,8 @@ def fit(r: int, steps: int = 300, init: str = "strassen", seed: int = 0, size: i
     prob = stl.Problem(m, k, n, r, stl.STL_F32)
     What = torch.empty((r, K, N), **dev)
     C = torch.empty((m, n), **dev)
-    Xhat = torch.empty((r, M, K), **dev)
-    Yhat = torch.empty((r, M, N), **dev)
+    Xhat = torch.empty(stl.stl_plane_elems(M, K, r), **dev)    # saved planes, layout private to the library
+    Yhat = torch.empty(stl.stl_plane_elems(M, N, r), **dev)
     dWhat = torch.empty((r, K, N), **dev)
     sizes = [stl.stl_workspace_bytes(prob, op) for op in (stl.STL_OP_FORWARD, stl.STL_OP_BACKWARD, stl.STL_OP_ENCODE_WEIGHT_BACKWARD)]
     ws = torch.empty(max(max(sizes), 16), dtype=torch.uint8, device="cuda")

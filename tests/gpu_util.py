@@ -24,6 +24,39 @@ def host(t):
     return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
 
 
+PG = stl.STL_PLANE_GROUP
+
+
+def group_planes(a):
+    """Plane-major (r, R, Cc) numpy -> the library's activation-side layout (groups of PG tile rows), flat."""
+    a = np.asarray(a)
+    r, R, Cc = a.shape
+    Rp = (R + PG - 1) // PG * PG
+    pad = np.zeros((r, Rp, Cc), dtype=a.dtype)
+    pad[:, :R] = a
+    return np.ascontiguousarray(pad.reshape(r, Rp // PG, PG, Cc).transpose(1, 0, 2, 3)).reshape(-1)
+
+
+def ungroup_planes(flat, r, R, Cc):
+    """Inverse of group_planes: flat grouped array -> plane-major (r, R, Cc)."""
+    Rp = (R + PG - 1) // PG * PG
+    a = np.asarray(flat).reshape(Rp // PG, r, PG, Cc).transpose(1, 0, 2, 3).reshape(r, Rp, Cc)
+    return np.ascontiguousarray(a[:, :R])
+
+
+def planes_buffer(r, R, Cc, dtype, fill=float("nan")):
+    return torch.full((stl.stl_plane_elems(R, Cc, r),), fill, dtype=TORCH_DT[dtype], device="cuda")
+
+
+def planes_to_dev(a, dtype):
+    """plane-major numpy (r, R, Cc) -> device tensor in the grouped layout"""
+    return dev(group_planes(np.asarray(a, dtype=np.float32)), dtype)
+
+
+def planes_to_host(t, r, R, Cc):
+    return ungroup_planes(host(t), r, R, Cc)
+
+
 def workspace(prob, op, flags=0):
     nbytes = stl.stl_workspace_bytes(prob, op, flags)
     return torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda"), nbytes
@@ -37,14 +70,14 @@ def forward(p, dtype, flags=0, save_yhat=False, save_xhat=False):
     prob = stl.Problem(m, k, n, r, STL_DT[dtype])
     X, What, E_X, D = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D"))
     C = torch.full((m, n), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
-    Y = torch.full((r, m // 4, N), float("nan"), dtype=TORCH_DT[dtype], device="cuda") if save_yhat else None
-    Xh = torch.full((r, m // 4, k // 4), float("nan"), dtype=TORCH_DT[dtype], device="cuda") if save_xhat else None
+    Y = planes_buffer(r, m // 4, N, dtype) if save_yhat else None
+    Xh = planes_buffer(r, m // 4, k // 4, dtype) if save_xhat else None
     ws, nbytes = workspace(prob, stl.STL_OP_FORWARD, flags)
     stl.stl_forward(prob, X, What, E_X, D, C, Xh, Y, ws, nbytes, flags)
     torch.cuda.synchronize()
     if save_xhat:
-        return host(C), host(Xh), host(Y)
-    return (host(C), host(Y)) if save_yhat else host(C)
+        return host(C), planes_to_host(Xh, r, m // 4, k // 4), planes_to_host(Y, r, m // 4, N)
+    return (host(C), planes_to_host(Y, r, m // 4, N)) if save_yhat else host(C)
 
 
 def backward(p, dtype, yhat=None, accumulate=0, init=None, skip=(), xhat=None):
@@ -53,8 +86,8 @@ def backward(p, dtype, yhat=None, accumulate=0, init=None, skip=(), xhat=None):
     n = 4 * N
     prob = stl.Problem(m, k, n, r, STL_DT[dtype])
     X, What, E_X, D, dC = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D", "dC"))
-    Y = dev(yhat, dtype) if yhat is not None else None
-    Xh = dev(xhat, dtype) if xhat is not None else None
+    Y = planes_to_dev(yhat, dtype) if yhat is not None else None
+    Xh = planes_to_dev(xhat, dtype) if xhat is not None else None
     dX = torch.full((m, k), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
     f32 = dict(dtype=torch.float32, device="cuda")
     if init is None:
@@ -96,12 +129,12 @@ def recode(Yhat1, D1, E2, dtype, flags=0, with_scratch=False):
     r2 = E2.shape[0]
     up = stl.Problem(4 * M, 4, 4 * N1, r1, STL_DT[dtype])          # k of the first layer plays no part in this step
     down = stl.Problem(4 * M, 4 * N1, 4, r2, STL_DT[dtype])
-    Y, D, E = dev(Yhat1, dtype), dev(D1, dtype), dev(E2, dtype)
-    Xh2 = torch.full((r2, M, N1), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
+    Y, D, E = planes_to_dev(Yhat1, dtype), dev(D1, dtype), dev(E2, dtype)
+    Xh2 = planes_buffer(r2, M, N1, dtype)
     H = torch.empty((4 * M, 4 * N1), dtype=TORCH_DT[dtype], device="cuda") if with_scratch else None
     stl.stl_recode(up, down, Y, D, E, Xh2, H, flags)
     torch.cuda.synchronize()
-    return host(Xh2)
+    return planes_to_host(Xh2, r2, M, N1)
 
 
 def encode_weight_backward(W, E_W, dWhat, dtype, accumulate=0, init=None, skip=()):

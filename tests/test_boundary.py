@@ -161,3 +161,20 @@ def test_misaligned_pointers_are_rejected():
     with pytest.raises(stl.StlError) as e:
         stl.stl_decode(prob, FAKE, FAKE, odd, 0, stream=0)
     assert e.value.status == 1
+
+
+def test_plane_layout_helpers():
+    """stl_plane_elems and the test-side converters agree with the layout the header states:
+    element (p, I, J) at ((I / 64) * r + p) * 64 * Cc + (I % 64) * Cc + J."""
+    import numpy as np
+    import gpu_util
+    assert stl.STL_PLANE_GROUP == 64
+    assert stl.stl_plane_elems(100, 8, 3) == 3 * 128 * 8
+    assert stl.stl_plane_elems(128, 5, 7) == 7 * 128 * 5
+    r, R, Cc = 3, 100, 8
+    a = np.arange(r * R * Cc, dtype=np.float64).reshape(r, R, Cc)
+    flat = gpu_util.group_planes(a)
+    assert flat.size == stl.stl_plane_elems(R, Cc, r)
+    for (p, I, J) in [(0, 0, 0), (2, 63, 7), (1, 64, 0), (2, 99, 3)]:
+        assert flat[((I // 64) * r + p) * 64 * Cc + (I % 64) * Cc + J] == a[p, I, J]
+    assert np.array_equal(gpu_util.ungroup_planes(flat, r, R, Cc), a)

@@ -81,18 +81,20 @@ def test_stage_entry_points(gu, dtype):
     prob = stl.Problem(m, k, n, r, gu.STL_DT[dtype])
     tdt = gu.TORCH_DT[dtype]
     X, What, E_X, D = (gu.dev(p[s], dtype) for s in ("X", "What", "E_X", "D"))
-    Xhat = torch.empty((r, m // 4, k // 4), dtype=tdt, device="cuda")
+    Xhat = gu.planes_buffer(r, m // 4, k // 4, dtype)
     stl.stl_encode_activation(prob, X, E_X, Xhat)
     torch.cuda.synchronize()
-    assert gu.rel(gu.host(Xhat), oracle.encode_x(p["X"], p["E_X"])) <= gu.TOL[dtype]
-    Yhat = torch.empty((r, m // 4, n // 4), dtype=tdt, device="cuda")
+    Xh = gu.planes_to_host(Xhat, r, m // 4, k // 4)
+    assert gu.rel(Xh, oracle.encode_x(p["X"], p["E_X"])) <= gu.TOL[dtype]
+    Yhat = gu.planes_buffer(r, m // 4, n // 4, dtype)
     stl.stl_plane_matmul(prob, Xhat, What, Yhat)
     torch.cuda.synchronize()
-    assert gu.rel(gu.host(Yhat), planes.plane_products(gu.host(Xhat), p["What"])) <= gu.TOL[dtype]
+    Yh = gu.planes_to_host(Yhat, r, m // 4, n // 4)
+    assert gu.rel(Yh, planes.plane_products(Xh, p["What"])) <= gu.TOL[dtype]
     C = torch.empty((m, n), dtype=tdt, device="cuda")
     stl.stl_decode(prob, Yhat, D, C)
     torch.cuda.synchronize()
-    assert gu.rel(gu.host(C), planes.decode(gu.host(Yhat), p["D"])) <= gu.TOL[dtype]
+    assert gu.rel(gu.host(C), planes.decode(Yh, p["D"])) <= gu.TOL[dtype]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -111,7 +113,7 @@ def test_gelu_entrywise_accuracy_fp32(gu):
     import paper_2503_12211_amd as stl
     h = np.linspace(-9.0, 9.0, 16 * 8 * 8).astype(np.float32).reshape(16, 8, 8)
     prob = stl.Problem(32, 32, 32, 16, stl.STL_F32)
-    Yhat, D = gu.dev(h, "f32"), gu.dev(np.eye(16, dtype=np.float32), "f32")
+    Yhat, D = gu.planes_to_dev(h, "f32"), gu.dev(np.eye(16, dtype=np.float32), "f32")
     C = torch.empty((32, 32), dtype=torch.float32, device="cuda")
     stl.stl_decode(prob, Yhat, D, C, stl.STL_FLAG_GELU)
     torch.cuda.synchronize()

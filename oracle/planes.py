@@ -114,3 +114,113 @@ def mlp_pair(X, What1, E_X1, D1, What2, E_X2, D2, t: int = 4, activation: str | 
     Yhat1 = plane_products(encode(X, E_X1, t), What1)
     Xhat2 = recode(Yhat1, D1, E_X2, activation, t)
     return decode(plane_products(Xhat2, What2), D2, t)
+
+
+# ------------------------------------------------------------------ both operands encoded at run time
+def aa_forward(A, B, E_A, E_B, D, nbatch: int = 1, t: int = 4):
+    """STL of two activations (the attention products of the Class-1 discussion, where neither operand is a
+    weight): the second operand is encoded at run time with E_B exactly as a weight is with E_W,
+        Bhat[p, L, J] = sum_q E_B[p, q] b[L, J, q],   C = decode_D( encode_{E_A}(A)[p] @ Bhat[p] ).
+    `nbatch` independent products (heads x images) are stacked along the rows: A is (nbatch*m, k), B is
+    (nbatch*k, n), C is (nbatch*m, n); the bases are shared by the whole batch."""
+    A = np.asarray(A, dtype=np.float64)
+    B = np.asarray(B, dtype=np.float64)
+    m, k = A.shape[0] // nbatch, B.shape[0] // nbatch
+    if A.shape[0] != nbatch * m or B.shape[0] != nbatch * k or A.shape[1] != k:
+        raise ValueError("stacked operands do not match nbatch")
+    out = []
+    for b in range(nbatch):
+        Bhat = encode(B[b * k:(b + 1) * k], E_B, t)
+        out.append(forward(A[b * m:(b + 1) * m], Bhat, E_A, D, t))
+    return np.concatenate(out, axis=0)
+
+
+def aa_backward(A, B, E_A, E_B, D, dC, nbatch: int = 1, t: int = 4):
+    """Gradients of sum_b <dC_b, C_b> for :func:`aa_forward`: (dA, dB, dE_A, dE_B, dD).  Chain rule through the
+    three steps for A (as for an activation) and through the run-time encoding for B (as for a weight); the
+    shared bases collect the sum over the batch."""
+    A = np.asarray(A, dtype=np.float64)
+    B = np.asarray(B, dtype=np.float64)
+    dC = np.asarray(dC, dtype=np.float64)
+    m, k = A.shape[0] // nbatch, B.shape[0] // nbatch
+    dA, dB = np.zeros_like(A), np.zeros_like(B)
+    dE_A, dE_B, dD = (np.zeros((np.asarray(D).shape[0], t * t)) for _ in range(3))
+    for b in range(nbatch):
+        Ab, Bb = A[b * m:(b + 1) * m], B[b * k:(b + 1) * k]
+        Bhat = encode(Bb, E_B, t)
+        dAb, dBhat, dEa, dDb = backward(Ab, Bhat, E_A, D, dC[b * m:(b + 1) * m], t)
+        dBb, dEb = encode_weight_backward(Bb, E_B, dBhat, t)
+        dA[b * m:(b + 1) * m] = dAb
+        dB[b * k:(b + 1) * k] = dBb
+        dE_A += dEa
+        dE_B += dEb
+        dD += dDb
+    return dA, dB, dE_A, dE_B, dD
+
+
+# ------------------------------------------------------------------ row counts that t does not divide
+def pad_rows(X, rows: int, t: int = 4):
+    """Appendix "More Details on STL Replacement in T2T-ViT", item 1: every image contributes `rows` token rows
+    (197 in the paper) and is extended with null rows to the next multiple of t (200).  X is the stack
+    (nimg*rows, k); returns (nimg*rows_pad, k)."""
+    X = np.asarray(X, dtype=np.float64)
+    nimg = X.shape[0] // rows
+    if X.shape[0] != nimg * rows:
+        raise ValueError("row count is not a multiple of the per-image rows")
+    rows_pad = -(-rows // t) * t
+    out = np.zeros((nimg, rows_pad, X.shape[1]))
+    out[:, :rows] = X.reshape(nimg, rows, -1)
+    return out.reshape(nimg * rows_pad, -1)
+
+
+def fold_rows(Y, fold, rows: int, t: int = 4):
+    """Same passage, the way back: the padded output (nimg*rows_pad, n) returns to (nimg*rows, n) rows.  Rows of
+    complete tile rows are kept; the last t padded rows of an image are combined linearly into its remaining
+    rho = rows - t*floor(rows/t) rows with the trainable coefficients `fold` (rho x t): the paper's case is
+    rho = 1 with 4 coefficients, and one combination per remaining row is the reading taken for rho = 2, 3.
+    With rows divisible by t nothing is folded."""
+    Y = np.asarray(Y, dtype=np.float64)
+    rows_pad = -(-rows // t) * t
+    nimg = Y.shape[0] // rows_pad
+    Y3 = Y.reshape(nimg, rows_pad, -1)
+    if rows_pad == rows:
+        return Y.copy()
+    fold = np.asarray(fold, dtype=np.float64)
+    body = rows_pad - t
+    if fold.shape != (rows - body, t):
+        raise ValueError("fold must be (rows mod t) x t")
+    out = np.empty((nimg, rows, Y3.shape[2]))
+    out[:, :body] = Y3[:, :body]
+    out[:, body:] = np.einsum("ra,iaj->irj", fold, Y3[:, body:])
+    return out.reshape(nimg * rows, -1)
+
+
+def ragged_forward(X, What, E_X, D, fold, rows: int, t: int = 4):
+    """STL layer on images of `rows` tokens each: pad with null rows, apply the operator, fold back."""
+    return fold_rows(forward(pad_rows(X, rows, t), What, E_X, D, t), fold, rows, t)
+
+
+def ragged_backward(X, What, E_X, D, fold, dC, rows: int, t: int = 4):
+    """Gradients of <dC, ragged_forward(...)>: (dX, dWhat, dE_X, dD, dfold).  The fold is linear, so its adjoint
+    spreads dC over the padded rows and dfold pairs the padded output with dC; gradients of null rows are
+    dropped."""
+    X = np.asarray(X, dtype=np.float64)
+    dC = np.asarray(dC, dtype=np.float64)
+    rows_pad = -(-rows // t) * t
+    nimg = X.shape[0] // rows
+    body = rows_pad - t
+    Xp = pad_rows(X, rows, t)
+    dC3 = dC.reshape(nimg, rows, -1)
+    dY = np.zeros((nimg, rows_pad, dC3.shape[2]))
+    if rows_pad == rows:
+        dY[:] = dC3
+        dfold = None
+    else:
+        fold = np.asarray(fold, dtype=np.float64)
+        Y3 = forward(Xp, What, E_X, D, t).reshape(nimg, rows_pad, -1)
+        dY[:, :body] = dC3[:, :body]
+        dY[:, body:] = np.einsum("ra,irj->iaj", fold, dC3[:, body:])
+        dfold = np.einsum("irj,iaj->ra", dC3[:, body:], Y3[:, body:])
+    dXp, dWhat, dE_X, dD = backward(Xp, What, E_X, D, dY.reshape(nimg * rows_pad, -1), t)
+    dX = dXp.reshape(nimg, rows_pad, -1)[:, :rows].reshape(nimg * rows, -1)
+    return dX, dWhat, dE_X, dD, dfold

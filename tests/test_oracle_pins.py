@@ -350,6 +350,144 @@ def test_mlp_pair_at_exact_bases_is_textbook_mlp(basis):
     assert rel(act, two) < 1e-12
 
 
+# --------------------------------------------------------------- both operands encoded at run time
+def test_aa_forward_brute_force_and_exact_basis():
+    """Two activations: (a) tile by tile from the operator's definition with the second operand encoded by E_B,
+    written with Python loops; (b) at the exact rank-49 basis every stacked product is A_b @ B_b."""
+    nb, m, k, n, r = 3, 8, 12, 4, 9
+    A = RNG.standard_normal((nb * m, k))
+    B = RNG.standard_normal((nb * k, n))
+    E_A, E_B, D = (RNG.standard_normal((r, 16)) for _ in range(3))
+    got = planes.aa_forward(A, B, E_A, E_B, D, nbatch=nb)
+    want = np.zeros((nb * m, n))
+    for b in range(nb):
+        for I in range(m // 4):
+            for J in range(n // 4):
+                acc = np.zeros(r)
+                for L in range(k // 4):
+                    a = A[b * m + 4 * I:b * m + 4 * I + 4, 4 * L:4 * L + 4].reshape(16)
+                    bb = B[b * k + 4 * L:b * k + 4 * L + 4, 4 * J:4 * J + 4].reshape(16)
+                    acc += (E_A @ a) * (E_B @ bb)
+                want[b * m + 4 * I:b * m + 4 * I + 4, 4 * J:4 * J + 4] = (D.T @ acc).reshape(4, 4)
+    assert rel(got, want) < 1e-13
+    E_A, E_B, D = bases.strassen_4x4()
+    got = planes.aa_forward(A, B, E_A, E_B, D, nbatch=nb)
+    for b in range(nb):
+        assert rel(got[b * m:(b + 1) * m], A[b * m:(b + 1) * m] @ B[b * k:(b + 1) * k]) < 1e-12
+    with pytest.raises(ValueError):
+        planes.aa_forward(A, B[:-4], E_A, E_B, D, nbatch=nb)
+
+
+def test_aa_backward_finite_differences_and_textbook():
+    """Gradients of sum_b <dC_b, C_b>: the loss is linear in each of A, B, E_A, E_B, D, so a one-sided difference
+    with any step is exact up to rounding; at the exact basis dA_b = dC_b B_b^T and dB_b = A_b^T dC_b."""
+    nb, m, k, n, r = 2, 8, 8, 12, 6
+    A = RNG.standard_normal((nb * m, k))
+    B = RNG.standard_normal((nb * k, n))
+    E_A, E_B, D = (RNG.standard_normal((r, 16)) * 0.5 for _ in range(3))
+    dC = RNG.standard_normal((nb * m, n))
+    args = [A, B, E_A, E_B, D]
+    loss = lambda a: float(np.sum(dC * planes.aa_forward(*a, nbatch=nb)))
+    grads = planes.aa_backward(A, B, E_A, E_B, D, dC, nbatch=nb)
+    base = loss(args)
+    for which, g in enumerate(grads):
+        assert g.shape == args[which].shape
+        for idx in [(0, 0), (args[which].shape[0] - 1, args[which].shape[1] - 1), (3, 5), (5, 2)]:
+            pert = [x.copy() for x in args]
+            pert[which][idx] += 0.5
+            assert abs((loss(pert) - base) / 0.5 - g[idx]) < 1e-9 * max(1.0, abs(g[idx])), (which, idx)
+    E_A, E_B, D = bases.strassen_4x4()
+    dA, dB, _, _, _ = planes.aa_backward(A, B, E_A, E_B, D, dC, nbatch=nb)
+    for b in range(nb):
+        Ab, Bb, dCb = A[b * m:(b + 1) * m], B[b * k:(b + 1) * k], dC[b * m:(b + 1) * m]
+        assert rel(dA[b * m:(b + 1) * m], dCb @ Bb.T) < 1e-12
+        assert rel(dB[b * k:(b + 1) * k], Ab.T @ dCb) < 1e-12
+
+
+# --------------------------------------------------------------- row counts that t does not divide
+def test_pad_and_fold_rows():
+    """197-token images (Class-1 appendix): 3 null rows are appended per image; on the way back complete tile rows
+    are copied and the last 4 rows become one row with 4 coefficients.  Written out with loops."""
+    rows, nimg, k = 9, 3, 4            # 9 = 2*4 + 1, the paper's 197 = 49*4 + 1 in small
+    X = RNG.standard_normal((nimg * rows, k))
+    Xp = planes.pad_rows(X, rows)
+    assert Xp.shape == (nimg * 12, k)
+    for i in range(nimg):
+        assert np.array_equal(Xp[12 * i:12 * i + 9], X[9 * i:9 * i + 9])
+        assert np.all(Xp[12 * i + 9:12 * i + 12] == 0.0)
+    Y = RNG.standard_normal((nimg * 12, 5))
+    c = RNG.standard_normal((1, 4))
+    F = planes.fold_rows(Y, c, rows)
+    assert F.shape == (nimg * 9, 5)
+    for i in range(nimg):
+        assert np.array_equal(F[9 * i:9 * i + 8], Y[12 * i:12 * i + 8])
+        want = sum(c[0, a] * Y[12 * i + 8 + a] for a in range(4))
+        assert np.allclose(F[9 * i + 8], want, rtol=0, atol=1e-14)
+    # rho = 3: one combination per remaining row; rows divisible by t: nothing happens
+    c3 = RNG.standard_normal((3, 4))
+    F3 = planes.fold_rows(Y, c3, 11)
+    assert np.allclose(F3[11 * 1 + 8:11 * 1 + 11], c3 @ Y[12 + 8:12 + 12], rtol=0, atol=1e-14)
+    assert np.array_equal(planes.fold_rows(Y, None, 12), Y)
+    with pytest.raises(ValueError):
+        planes.fold_rows(Y, np.zeros((2, 4)), rows)
+    with pytest.raises(ValueError):
+        planes.pad_rows(X[:-1], rows)
+
+
+def test_ragged_forward_closed_forms():
+    """At the exact basis the padded operator is X_pad @ W, whose null rows are zero: the folded last row is
+    fold[0] * (x_last @ W) and all other rows are X @ W.  With a generic basis the null rows of the last tile row
+    do produce output (tiles mix rows), and the fold must use all four: checked against the tile-by-tile oracle."""
+    rows, nimg, k, n = 5, 2, 8, 12
+    X = RNG.standard_normal((nimg * rows, k))
+    W = RNG.standard_normal((k, n))
+    c = RNG.standard_normal((1, 4))
+    E_X, E_W, D = bases.strassen_4x4()
+    got = planes.ragged_forward(X, oracle.encode_weight(W, E_W), E_X, D, c, rows)
+    want = X @ W
+    for i in range(nimg):
+        want[rows * i + 4] *= c[0, 0]
+    assert rel(got, want) < 1e-12
+    r = 7
+    E_X, E_W, D = (RNG.standard_normal((r, 16)) for _ in range(3))
+    What = oracle.encode_weight(W, E_W)
+    got = planes.ragged_forward(X, What, E_X, D, c, rows)
+    Xp = np.zeros((nimg * 8, k))
+    for i in range(nimg):
+        Xp[8 * i:8 * i + 5] = X[5 * i:5 * i + 5]
+    Yp = oracle.forward(Xp, What, E_X, D)
+    assert np.abs(Yp[5:8]).max() > 1e-3                      # null rows are not silent under a generic basis
+    for i in range(nimg):
+        assert rel(got[5 * i:5 * i + 4], Yp[8 * i:8 * i + 4]) < 1e-13
+        assert rel(got[5 * i + 4], c[0] @ Yp[8 * i + 4:8 * i + 8]) < 1e-13
+
+
+def test_ragged_backward_finite_differences():
+    """The loss <dC, ragged_forward> is linear in X, What, E_X, D and fold: one-sided differences are exact."""
+    rows, nimg, k, n, r = 6, 2, 8, 4, 5          # rho = 2
+    X = RNG.standard_normal((nimg * rows, k))
+    What = RNG.standard_normal((r, k // 4, n // 4))
+    E_X, D = (RNG.standard_normal((r, 16)) * 0.5 for _ in range(2))
+    fold = RNG.standard_normal((2, 4))
+    dC = RNG.standard_normal((nimg * rows, n))
+    args = [X, What, E_X, D, fold]
+    loss = lambda a: float(np.sum(dC * planes.ragged_forward(*a, rows)))
+    grads = planes.ragged_backward(X, What, E_X, D, fold, dC, rows)
+    base = loss(args)
+    for which, g in enumerate(grads):
+        assert g.shape == args[which].shape
+        flat = g.reshape(-1)
+        for j in sorted({0, flat.size - 1, flat.size // 2, flat.size // 3}):
+            idx = np.unravel_index(j, g.shape)
+            pert = [x.copy() for x in args]
+            pert[which][idx] += 0.5
+            assert abs((loss(pert) - base) / 0.5 - g[idx]) < 1e-9 * max(1.0, abs(g[idx])), (which, idx)
+    # rows divisible by t: identical to the plain operator, no fold gradient
+    g4 = planes.ragged_backward(X[:8], What, E_X, D, None, dC[:8], 4)
+    ref = planes.backward(X[:8], What, E_X, D, dC[:8])
+    assert g4[4] is None and all(rel(a, b) < 1e-14 for a, b in zip(g4[:4], ref))
+
+
 def test_gelu_values():
     """Exact-erf GELU against closed-form values: gelu(0)=0, gelu(x)-gelu(-x)=x, gelu(1)=Phi(1)."""
     assert planes.gelu(0.0) == 0.0

@@ -183,6 +183,43 @@ stl_status_t stl_mlp_forward(const stl_problem_t *up, const stl_problem_t *down,
 stl_status_t stl_recode(const stl_problem_t *up, const stl_problem_t *down, const void *Yhat1,
                         const void *D1, const void *E_X2, void *Xhat2, void *H, int flags, void *stream);
 
+/*
+ * STL of two activations, C_b = A_b <> B_b for b < nbatch (the attention products Q K^T and A V of the
+ * Class-1 discussion: "activation x activation", where neither operand is a stored weight).  The second
+ * operand is encoded at run time with E_B exactly as a weight is with E_W (plane definition before Claim
+ * 3.4), the first with E_A as an activation:
+ *     vec(C_b{I,J}) = D^T sum_L (E_A vec A_b{I,L}) (.) (E_B vec B_b{L,J}).
+ * The nbatch independent problems (heads x images) are stacked along the rows and share the bases:
+ * A: (nbatch*m) x k, B: (nbatch*k) x n, C: (nbatch*m) x n, prob giving m, k, n of ONE problem.
+ * All plane tensors are activation-side (grouped layout) over the stacked tile rows:
+ *   Ahat stl_plane_elems(nbatch*M, K, r), Bhat stl_plane_elems(nbatch*K, N, r), Yhat stl_plane_elems(nbatch*M, N, r)
+ * elements.  *_save: NULL or a buffer that receives the tensor for stl_aa_backward.
+ * flags: 0 or STL_FLAG_GELU.  ws / ws_bytes: at least stl_aa_workspace_bytes(prob, nbatch, STL_OP_FORWARD).
+ * nbatch*m and nbatch*k may not exceed 2^24 (INVALID_ARG).
+ */
+size_t stl_aa_workspace_bytes(const stl_problem_t *prob, int64_t nbatch, int op);
+stl_status_t stl_aa_forward(const stl_problem_t *prob, int64_t nbatch, const void *A, const void *B,
+                            const void *E_A, const void *E_B, const void *D, void *C, void *Ahat_save,
+                            void *Bhat_save, void *Yhat_save, void *ws, size_t ws_bytes, int flags,
+                            void *stream);
+/*
+ * Backward of sum_b <dC_b, C_b> for stl_aa_forward (chain rule; A's side as in stl_backward, B's side as in
+ * stl_backward followed by stl_encode_weight_backward, per problem):
+ *   dYhat = encode_D(dC)              dD   += Yhat (x) dc
+ *   dAhat_b[p] = dYhat_b[p] Bhat_b[p]^T   dA = decode_{E_A}(dAhat)   dE_A += dAhat (x) a
+ *   dBhat_b[p] = Ahat_b[p]^T dYhat_b[p]   dB = decode_{E_B}(dBhat)   dE_B += dBhat (x) b
+ * dC: (nbatch*m) x n (in).  *_saved: NULL (recomputed) or what stl_aa_forward wrote.  dA, dB: storage dtype
+ * (out); dE_A, dE_B, dD: r x 16 fp32 (out), summed over the batch; any output may be NULL.  dBhat is kept in the
+ * storage dtype (it is a per-problem intermediate like dAhat, not an accumulated weight gradient).
+ * accumulate: as in stl_backward, for dE_A, dE_B, dD.
+ * ws / ws_bytes: at least stl_aa_workspace_bytes(prob, nbatch, STL_OP_BACKWARD).
+ */
+stl_status_t stl_aa_backward(const stl_problem_t *prob, int64_t nbatch, const void *A, const void *B,
+                             const void *E_A, const void *E_B, const void *D, const void *dC,
+                             const void *Ahat_saved, const void *Bhat_saved, const void *Yhat_saved, void *dA,
+                             void *dB, float *dE_A, float *dE_B, float *dD, int accumulate, void *ws,
+                             size_t ws_bytes, void *stream);
+
 /* Static text for a status code. */
 const char *stl_status_string(stl_status_t status);
 /* Text of the last error raised on the calling thread ("" if none).  Thread-local storage. */

@@ -22,6 +22,7 @@ STL_FLAG_GELU = 0x100
 SYMBOLS = (
     "stl_plane_elems", "stl_workspace_bytes", "stl_encode_weight", "stl_encode_weight_backward", "stl_forward", "stl_backward", "stl_encode_activation",
     "stl_plane_matmul", "stl_decode", "stl_mlp_workspace_bytes", "stl_mlp_forward", "stl_recode",
+    "stl_aa_workspace_bytes", "stl_aa_forward", "stl_aa_backward",
     "stl_status_string", "stl_last_error", "stl_version",
 )
 
@@ -82,7 +83,11 @@ def _load():
     lib.stl_mlp_workspace_bytes.argtypes = [pp, pp, ctypes.c_int]
     lib.stl_mlp_forward.argtypes = [pp, pp, _P, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, ctypes.c_int, _P]
     lib.stl_recode.argtypes = [pp, pp, _P, _P, _P, _P, _P, ctypes.c_int, _P]
-    for name in ("stl_encode_weight", "stl_forward", "stl_backward", "stl_encode_activation", "stl_plane_matmul",
+    lib.stl_aa_workspace_bytes.restype = ctypes.c_size_t
+    lib.stl_aa_workspace_bytes.argtypes = [pp, ctypes.c_int64, ctypes.c_int]
+    lib.stl_aa_forward.argtypes = [pp, ctypes.c_int64] + [_P] * 10 + [ctypes.c_size_t, ctypes.c_int, _P]
+    lib.stl_aa_backward.argtypes = [pp, ctypes.c_int64] + [_P] * 14 + [ctypes.c_int, _P, ctypes.c_size_t, _P]
+    for name in ("stl_aa_forward", "stl_aa_backward", "stl_encode_weight", "stl_forward", "stl_backward", "stl_encode_activation", "stl_plane_matmul",
                  "stl_decode", "stl_mlp_forward", "stl_recode", "stl_encode_weight_backward"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stl_status_string.restype = ctypes.c_char_p
@@ -194,3 +199,21 @@ def stl_recode(up: Problem, down: Problem, Yhat1, D1, E_X2, Xhat2, H=None, flags
                stream=None) -> None:
     _check(_load().stl_recode(ctypes.byref(up.c()), ctypes.byref(down.c()), _ptr(Yhat1), _ptr(D1), _ptr(E_X2),
                               _ptr(Xhat2), _ptr(H), flags, _stream(stream)))
+
+
+def stl_aa_workspace_bytes(prob: Problem, nbatch: int, op: int) -> int:
+    return int(_load().stl_aa_workspace_bytes(ctypes.byref(prob.c()), nbatch, op))
+
+
+def stl_aa_forward(prob: Problem, nbatch: int, A, B, E_A, E_B, D, C, Ahat_save=None, Bhat_save=None, Yhat_save=None,
+                   ws=None, ws_bytes: int = 0, flags: int = 0, stream=None) -> None:
+    _check(_load().stl_aa_forward(ctypes.byref(prob.c()), nbatch, _ptr(A), _ptr(B), _ptr(E_A), _ptr(E_B), _ptr(D), _ptr(C),
+                                  _ptr(Ahat_save), _ptr(Bhat_save), _ptr(Yhat_save), _ptr(ws), ws_bytes, flags,
+                                  _stream(stream)))
+
+
+def stl_aa_backward(prob: Problem, nbatch: int, A, B, E_A, E_B, D, dC, Ahat_saved, Bhat_saved, Yhat_saved, dA, dB, dE_A,
+                    dE_B, dD, accumulate: int = 0, ws=None, ws_bytes: int = 0, stream=None) -> None:
+    _check(_load().stl_aa_backward(ctypes.byref(prob.c()), nbatch, _ptr(A), _ptr(B), _ptr(E_A), _ptr(E_B), _ptr(D), _ptr(dC),
+                                   _ptr(Ahat_saved), _ptr(Bhat_saved), _ptr(Yhat_saved), _ptr(dA), _ptr(dB), _ptr(dE_A),
+                                   _ptr(dE_B), _ptr(dD), accumulate, _ptr(ws), ws_bytes, _stream(stream)))

@@ -194,6 +194,64 @@ MlpWs mlp_layout(const stl_problem_t *up, const Dims &d1, const Dims &d2, int va
     return w;
 }
 
+// both operands encoded at run time, nbatch problems stacked along the rows
+struct AaWs {
+    size_t ahat, bhat, yhat, dyhat, dahat, dbhat, part, total;
+};
+
+size_t stacked_planes_bytes(const Dims &d, int64_t rows, int cols)
+{
+    const size_t rp = ((size_t)rows + PG - 1) / PG * PG;
+    return align256((size_t)d.r * rp * cols * d.es);
+}
+
+AaWs aa_layout(const Dims &d, int64_t nb, bool backward)
+{
+    AaWs w{};
+    size_t off = 0;
+    const size_t pa = stacked_planes_bytes(d, nb * d.M, d.K), pb = stacked_planes_bytes(d, nb * d.K, d.N),
+                 py = stacked_planes_bytes(d, nb * d.M, d.N);
+    w.ahat = off;
+    off += pa;
+    w.bhat = off;
+    off += pb;
+    w.yhat = off;
+    off += py;
+    if (backward) {
+        w.dyhat = off;
+        off += py;
+        w.dahat = off;
+        off += pa;
+        w.dbhat = off;
+        off += pb;
+        int nblk = 1;
+        const int64_t Rs[3] = {nb * d.M, nb * d.M, nb * d.K};
+        const int Cs[3] = {d.N, d.K, d.N};
+        for (int i = 0; i < 3; ++i) {
+            const int a = stl::outer_reduce_blocks(Rs[i] * Cs[i]), b = stl::decode_outer_blocks((int)Rs[i], Cs[i]),
+                      c = stl::encode_outer_blocks((int)Rs[i], Cs[i]);
+            nblk = a > nblk ? a : nblk;
+            nblk = b > nblk ? b : nblk;
+            nblk = c > nblk ? c : nblk;
+        }
+        w.part = off;
+        off += align256((size_t)nblk * d.r * 16 * sizeof(float));
+    }
+    w.total = off;
+    return w;
+}
+
+stl_status_t check_batch(const stl_problem_t *p, const Dims &d, int64_t nb)
+{
+    if (nb < 1) return fail(STL_ERR_INVALID_ARG, "nbatch=%lld must be positive", (long long)nb);
+    if (nb * p->m > kMaxDim || nb * p->k > kMaxDim)
+        return fail(STL_ERR_INVALID_ARG, "stacked rows nbatch*m or nbatch*k larger than %lld", (long long)kMaxDim);
+    const double big = 1099511627776.0;
+    if ((double)nb * d.r * d.M * d.K > big || (double)nb * d.r * d.M * d.N > big || (double)nb * d.r * d.K * d.N > big)
+        return fail(STL_ERR_INVALID_ARG, "stacked plane tensors too large");
+    return STL_OK;
+}
+
 #define STL_HIP(call, what)                                \
     do {                                                   \
         hipError_t e__ = (call);                           \
@@ -516,6 +574,120 @@ stl_status_t stl_mlp_forward(const stl_problem_t *up, const stl_problem_t *down,
     stl::GemmDesc g2{d2.M, d2.N, d2.K, d2.r, false, true, false, false, PG, 0, PG};
     STL_HIP(stl::launch_plane_gemm(dt, g2, xhat2, What2, yhat2, s), "pair/plane products 2");
     STL_HIP(stl::launch_decode(dt, yhat2, D2, C, d2.M, d2.N, d2.r, false, PG, s), "pair/decode 2");
+    return STL_OK;
+}
+
+size_t stl_aa_workspace_bytes(const stl_problem_t *prob, int64_t nbatch, int op)
+{
+    Dims d;
+    if (check_problem(prob, &d) != STL_OK || check_batch(prob, d, nbatch) != STL_OK) return 0;
+    if (op == STL_OP_FORWARD) return aa_layout(d, nbatch, false).total;
+    if (op == STL_OP_BACKWARD) return aa_layout(d, nbatch, true).total;
+    fail(STL_ERR_INVALID_ARG, "stl_aa_workspace_bytes: op must be STL_OP_FORWARD or STL_OP_BACKWARD");
+    return 0;
+}
+
+stl_status_t stl_aa_forward(const stl_problem_t *prob, int64_t nbatch, const void *A, const void *B, const void *E_A,
+                            const void *E_B, const void *D, void *C, void *Ahat_save, void *Bhat_save, void *Yhat_save,
+                            void *ws, size_t ws_bytes, int flags, void *stream)
+{
+    Dims d;
+    stl_status_t st = check_problem(prob, &d);
+    if (st != STL_OK) return st;
+    st = check_batch(prob, d, nbatch);
+    if (st != STL_OK) return st;
+    if (flags & ~STL_FLAG_GELU) return fail(STL_ERR_UNSUPPORTED, "stl_aa_forward: unknown flag bits 0x%x", flags);
+    if (!A || !B || !E_A || !E_B || !D || !C) return fail(STL_ERR_INVALID_ARG, "stl_aa_forward: NULL pointer");
+    if (any_misaligned(A, B, E_A, E_B, D, C, Ahat_save, Bhat_save, Yhat_save))
+        return fail(STL_ERR_INVALID_ARG, "stl_aa_forward: pointer not 16-byte aligned");
+    const AaWs w = aa_layout(d, nbatch, false);
+    if (!ws || ws_bytes < w.total)
+        return fail(STL_ERR_WORKSPACE, "stl_aa_forward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
+    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_aa_forward: workspace is not 16-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    const int dt = prob->dtype, nb = (int)nbatch;
+    char *base = (char *)ws;
+    void *ahat = Ahat_save ? Ahat_save : (void *)(base + w.ahat);
+    void *bhat = Bhat_save ? Bhat_save : (void *)(base + w.bhat);
+    void *yhat = Yhat_save ? Yhat_save : (void *)(base + w.yhat);
+    // the stack of first operands is one tall matrix for the tile maps; so is the stack of second operands
+    STL_HIP(stl::launch_encode(dt, A, E_A, ahat, nb * d.M, d.K, d.r, PG, s), "aa_forward/encode A");
+    STL_HIP(stl::launch_encode(dt, B, E_B, bhat, nb * d.K, d.N, d.r, PG, s), "aa_forward/encode B");
+    stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false, PG, PG, PG, nb};
+    STL_HIP(stl::launch_plane_gemm(dt, g, ahat, bhat, yhat, s), "aa_forward/plane products");
+    STL_HIP(stl::launch_decode(dt, yhat, D, C, nb * d.M, d.N, d.r, (flags & STL_FLAG_GELU) != 0, PG, s), "aa_forward/decode");
+    return STL_OK;
+}
+
+stl_status_t stl_aa_backward(const stl_problem_t *prob, int64_t nbatch, const void *A, const void *B, const void *E_A,
+                             const void *E_B, const void *D, const void *dC, const void *Ahat_saved, const void *Bhat_saved,
+                             const void *Yhat_saved, void *dA, void *dB, float *dE_A, float *dE_B, float *dD, int accumulate,
+                             void *ws, size_t ws_bytes, void *stream)
+{
+    Dims d;
+    stl_status_t st = check_problem(prob, &d);
+    if (st != STL_OK) return st;
+    st = check_batch(prob, d, nbatch);
+    if (st != STL_OK) return st;
+    if (!A || !B || !E_A || !E_B || !D || !dC) return fail(STL_ERR_INVALID_ARG, "stl_aa_backward: NULL input pointer");
+    if (any_misaligned(A, B, E_A, E_B, D, dC, Ahat_saved, Bhat_saved, Yhat_saved, dA, dB, dE_A, dE_B, dD))
+        return fail(STL_ERR_INVALID_ARG, "stl_aa_backward: pointer not 16-byte aligned");
+    if (accumulate != 0 && accumulate != 1) return fail(STL_ERR_INVALID_ARG, "stl_aa_backward: accumulate must be 0 or 1");
+    const AaWs w = aa_layout(d, nbatch, true);
+    if (!ws || ws_bytes < w.total)
+        return fail(STL_ERR_WORKSPACE, "stl_aa_backward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
+    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_aa_backward: workspace is not 16-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    const int dt = prob->dtype, nb = (int)nbatch;
+    const int RA = nb * d.M, RB = nb * d.K;      // stacked tile rows of A (and C) and of B
+    char *base = (char *)ws;
+    float *part = (float *)(base + w.part);
+    void *dyhat = base + w.dyhat, *dahat = base + w.dahat, *dbhat = base + w.dbhat;
+
+    const bool want_a = dA || dE_A, want_b = dB || dE_B;
+    const void *ahat = Ahat_saved, *bhat = Bhat_saved, *yhat = Yhat_saved;
+    if (!ahat && (want_b || (dD && !yhat))) {
+        STL_HIP(stl::launch_encode(dt, A, E_A, base + w.ahat, RA, d.K, d.r, PG, s), "aa_backward/encode A");
+        ahat = base + w.ahat;
+    }
+    if (!bhat && (want_a || (dD && !yhat))) {
+        STL_HIP(stl::launch_encode(dt, B, E_B, base + w.bhat, RB, d.N, d.r, PG, s), "aa_backward/encode B");
+        bhat = base + w.bhat;
+    }
+    if (dD && !yhat) {
+        stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false, PG, PG, PG, nb};
+        STL_HIP(stl::launch_plane_gemm(dt, g, ahat, bhat, base + w.yhat, s), "aa_backward/recompute Yhat");
+        yhat = base + w.yhat;
+    }
+    if (dD && stl::encode_outer_eligible(dt, d.N)) {
+        STL_HIP(stl::launch_encode_outer(dC, D, dyhat, yhat, dD, part, RA, d.N, d.r, accumulate, PG, s), "aa_backward/dYhat + dD");
+    } else {
+        STL_HIP(stl::launch_encode(dt, dC, D, dyhat, RA, d.N, d.r, PG, s), "aa_backward/encode dC");
+        if (dD) STL_HIP(stl::launch_outer_reduce(dt, yhat, dC, dD, part, RA, d.N, d.r, accumulate, PG, s), "aa_backward/dD");
+    }
+    if (want_a) {
+        // dAhat[b][p] = dYhat[b][p] * Bhat[b][p]^T, then back through the encoding of A
+        stl::GemmDesc g{d.M, d.K, d.N, d.r, false, false, false, false, PG, PG, PG, nb};
+        STL_HIP(stl::launch_plane_gemm(dt, g, dyhat, bhat, dahat, s), "aa_backward/dAhat");
+        if (dA && dE_A && stl::decode_outer_eligible(dt, d.K)) {
+            STL_HIP(stl::launch_decode_outer(dahat, E_A, dA, A, dE_A, part, RA, d.K, d.r, accumulate, PG, s), "aa_backward/dA + dE_A");
+        } else {
+            if (dA) STL_HIP(stl::launch_decode(dt, dahat, E_A, dA, RA, d.K, d.r, false, PG, s), "aa_backward/decode dA");
+            if (dE_A) STL_HIP(stl::launch_outer_reduce(dt, dahat, A, dE_A, part, RA, d.K, d.r, accumulate, PG, s), "aa_backward/dE_A");
+        }
+    }
+    if (want_b) {
+        // dBhat[b][p] = Ahat[b][p]^T * dYhat[b][p] in the storage type (one problem each, nothing accumulates over the
+        // batch), then back through the encoding of B
+        stl::GemmDesc g{d.K, d.N, d.M, d.r, true, true, false, false, PG, PG, PG, nb};
+        STL_HIP(stl::launch_plane_gemm(dt, g, ahat, dyhat, dbhat, s), "aa_backward/dBhat");
+        if (dB && dE_B && stl::decode_outer_eligible(dt, d.N)) {
+            STL_HIP(stl::launch_decode_outer(dbhat, E_B, dB, B, dE_B, part, RB, d.N, d.r, accumulate, PG, s), "aa_backward/dB + dE_B");
+        } else {
+            if (dB) STL_HIP(stl::launch_decode(dt, dbhat, E_B, dB, RB, d.N, d.r, false, PG, s), "aa_backward/decode dB");
+            if (dE_B) STL_HIP(stl::launch_outer_reduce(dt, dbhat, B, dE_B, part, RB, d.N, d.r, accumulate, PG, s), "aa_backward/dE_B");
+        }
+    }
     return STL_OK;
 }
 

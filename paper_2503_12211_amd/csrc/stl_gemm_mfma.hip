@@ -28,9 +28,10 @@ __device__ __forceinline__ int lds_off(int row, int c) { return row * (BK * 2) +
 struct Lay {
     int pg, batch, p;
     long ld;
+    int row0;   // first stored row of this problem inside the stacked operand
     __device__ __forceinline__ size_t off(int row) const
     {
-        return plane_row_base(row, pg, batch, (int)ld) + (size_t)p * pg * ld;
+        return plane_row_base(row0 + row, pg, batch, (int)ld) + (size_t)p * pg * ld;
     }
 };
 
@@ -117,7 +118,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(const 
                                                                           const bf16_t *__restrict__ B,
                                                                           TO *__restrict__ Out, int Mi, int Nj, int Kl,
                                                                           int tiles_m, int tiles_n, int total, int a_pg,
-                                                                          int b_pg, int o_pg)
+                                                                          int b_pg, int o_pg, int batch)
 {
     constexpr int NT = WAVES_M * WAVES_N * 64;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -129,12 +130,13 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_mfma_kernel(const 
     int bid = blockIdx.x;
     if ((total & 7) == 0) bid = (bid & 7) * (total >> 3) + (bid >> 3);
     const int per_plane = tiles_m * tiles_n;
-    const int p = bid / per_plane;
-    const int rem = bid - p * per_plane;
+    const int q = bid / per_plane;                    // (stacked problem, plane)
+    const int rem = bid - q * per_plane;
     const int i0 = (rem / tiles_n) * BM, j0 = (rem % tiles_n) * BN;
+    const int pb = q / batch, p = q - pb * batch;
 
-    const int batch = total / per_plane;
-    const Lay lda{a_pg, batch, p, A_T ? Mi : Kl}, ldb{b_pg, batch, p, B_T ? Nj : Kl}, ldo{o_pg, batch, p, Nj};
+    const Lay lda{a_pg, batch, p, A_T ? Mi : Kl, pb * (A_T ? Kl : Mi)}, ldb{b_pg, batch, p, B_T ? Nj : Kl, pb * (B_T ? Kl : Nj)},
+        ldo{o_pg, batch, p, Nj, pb * Mi};
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -237,8 +239,8 @@ bool plane_gemm_mfma_eligible(const GemmDesc &g)
     if (g.Mi < 1 || g.Nj < 1 || g.Kl < 1 || g.batch < 1) return false;
     if (g.accumulate && !g.out_f32) return false;
     // instantiated operand forms: forward [i][l]x[l][j], input gradient [i][l]x[j][l] (storage out),
-    // weight gradient [l][i]x[l][j] (fp32 out)
-    if (g.out_f32 ? !(g.a_kmajor && g.b_kmajor) : g.a_kmajor) return false;
+    // weight gradient [l][i]x[l][j] (fp32 out, or storage out for a run-time encoded second operand)
+    if (g.a_kmajor ? !g.b_kmajor : g.out_f32) return false;
     // 16-byte global loads along each operand's contiguous dimension
     if (g.Mi % 8 || g.Nj % 8 || g.Kl % 8) return false;
     return true;
@@ -257,11 +259,11 @@ static hipError_t launch_cfg(const GemmDesc &g, const void *A, const void *B, vo
         attr_set = true;
     }
     const int tiles_m = (g.Mi + BM - 1) / BM, tiles_n = (g.Nj + BN - 1) / BN;
-    const long total = (long)tiles_m * tiles_n * g.batch;
+    const long total = (long)tiles_m * tiles_n * g.batch * g.nb;
     if (total > 0x7fffffffL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(WAVES_M * WAVES_N * 64), smem, s, (const bf16_t *)A,
                        (const bf16_t *)B, (TO *)Out, g.Mi, g.Nj, g.Kl, tiles_m, tiles_n, (int)total, g.a_rows_per_group(),
-                       g.b_rows_per_group(), g.o_rows_per_group());
+                       g.b_rows_per_group(), g.o_rows_per_group(), g.batch);
     return hipGetLastError();
 }
 
@@ -288,6 +290,7 @@ hipError_t launch_plane_gemm_mfma(const GemmDesc &g, const void *A, const void *
                                 : launch_shape<true, true, float, false>(g, A, B, Out, s);
         return hipErrorInvalidValue;  // only the weight-gradient product stores fp32
     }
+    if (g.a_kmajor && g.b_kmajor) return launch_shape<true, true, bf16_t, false>(g, A, B, Out, s);
     if (!g.a_kmajor && g.b_kmajor) return launch_shape<false, true, bf16_t, false>(g, A, B, Out, s);
     if (!g.a_kmajor && !g.b_kmajor) return launch_shape<false, false, bf16_t, false>(g, A, B, Out, s);
     return hipErrorInvalidValue;

@@ -58,11 +58,12 @@ struct Src {
     int kpos, pg;
     // base: the whole batched operand; plane p of `batch`; stored rows come in groups of pg (see plane_row_base), and a
     // stage's 32 stored rows of the [l][row] form never straddle two groups (pg % 32 == 0)
+    // roff: first stored row of this problem inside the stacked operand (a multiple of 32 for the [l][row] form)
     __device__ __forceinline__ void init(const bf16_t *base, long ld, int row0, int rows_total, int wave, int lane, int plane,
-                                         int batch, int pg_)
+                                         int batch, int pg_, int roff)
     {
         pg = pg_;
-        kpos = 0;
+        kpos = roff % pg_;
         const size_t poff = (size_t)plane * pg * ld;
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
@@ -71,12 +72,12 @@ struct Src {
                 const int row = 16 * q + (lane >> 2), c = (lane & 3) ^ fswz<SWZ>(row);
                 int gr = row0 + row;
                 gr = gr < rows_total ? gr : rows_total - 1;   // rows past the edge feed only discarded outputs
-                p[j] = base + plane_row_base(gr, pg, batch, (int)ld) + poff + 8 * c;
+                p[j] = base + plane_row_base(roff + gr, pg, batch, (int)ld) + poff + 8 * c;
             } else {
                 const int k = (64 / CPR) * q + lane / CPR, nc = (lane % CPR) ^ gswz(k);
                 int gc = row0 + 8 * nc;
                 gc = gc < rows_total ? gc : rows_total - 8;
-                p[j] = base + plane_row_base(k, pg, batch, (int)ld) + poff + gc;
+                p[j] = base + plane_row_base(roff + k, pg, batch, (int)ld) + poff + gc;
             }
         }
         step = KMAJOR ? (long)BKS * ld : BKS;
@@ -236,7 +237,7 @@ __device__ unsigned long long g_timeline[8192 * 4];
 template <int WAVES_M, int WAVES_N, int NS, int SWZ, bool A_T, bool B_T, typename TO, bool ACC>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B,
                                                         TO *__restrict__ Out, int Mi, int Nj, int Kl, int tiles_m,
-                                                        int tiles_n, int total, int dbg_arg, int a_pg, int b_pg, int o_pg)
+                                                        int tiles_n, int total, int dbg_arg, int a_pg, int b_pg, int o_pg, int batch)
 {
     // Timing-only ablation switches (they skip parts of the kernel and give wrong results): compiled in only with
     // -DSTL_GEMM_ABLATE; in the normal build dbg is the constant 0 and every test below folds away.
@@ -262,7 +263,6 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int per_plane = tiles_m * tiles_n;
-    const int batch = total / per_plane;
     const int nks = Kl / BKS;
     const uint32_t smem_lds = (uint32_t)(uintptr_t)STL_LDS(smem);
 
@@ -273,11 +273,13 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
 
     // block list: virtual block id v -> (plane, block row, block column); consecutive blocks of a plane are
     // dealt to one XCD (hardware deals workgroup ids round-robin over the 8 XCDs)
-    auto locate = [&](int v, int &p, int &i0, int &j0) {
+    auto locate = [&](int v, int &pb, int &p, int &i0, int &j0) {
         int lid = v;
         if ((total & 7) == 0 && (gridDim.x & 7) == 0) lid = (v & 7) * (total >> 3) + (v >> 3);
-        p = lid / per_plane;
-        const int rem = lid - p * per_plane;
+        const int q = lid / per_plane;               // (stacked problem, plane)
+        const int rem = lid - q * per_plane;
+        pb = q / batch;
+        p = q - pb * batch;
         i0 = (rem / tiles_n) * BM;
         j0 = (rem % tiles_n) * BN;
     };
@@ -285,10 +287,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
     Src<A_T, SWZ, BM, NW> sa;
     Src<B_T, SWZ, BN, NW> sb;
     auto start_block = [&](int v) {      // point the DMA sources at block v and put its first NS-1 stages in flight
-        int p, i0, j0;
-        locate(v, p, i0, j0);
-        sa.init(A, A_T ? Mi : Kl, i0, Mi, wave, lane, p, batch, a_pg);
-        sb.init(B, B_T ? Nj : Kl, j0, Nj, wave, lane, p, batch, b_pg);
+        int pb, p, i0, j0;
+        locate(v, pb, p, i0, j0);
+        sa.init(A, A_T ? Mi : Kl, i0, Mi, wave, lane, p, batch, a_pg, pb * (A_T ? Kl : Mi));
+        sb.init(B, B_T ? Nj : Kl, j0, Nj, wave, lane, p, batch, b_pg, pb * (B_T ? Kl : Nj));
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s) {
             if (s < nks) {
@@ -302,8 +304,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
     if (v < total) start_block(v);
 
     for (; v < total; v += gridDim.x) {
-        int p, i0, j0;
-        locate(v, p, i0, j0);
+        int pb, p, i0, j0;
+        locate(v, pb, p, i0, j0);
 
         f32x16_t acc[FM][FN];
 #pragma unroll
@@ -434,7 +436,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
                 // same wavefront wrote the slab; LDS operations of a wavefront complete in order
                 asm volatile("" ::: "memory");
                 const int gi_base = i0 + wm * WM + a * 32 + pass * RP;
-                const size_t row_off = plane_row_base(gi_base < Mi ? gi_base : 0, o_pg, batch, Nj);
+                const size_t row_off = plane_row_base(pb * Mi + (gi_base < Mi ? gi_base : 0), o_pg, batch, Nj);
                 const int gj = j0 + wn * WN + (lane % LPR) * (16 / ES);
 #pragma unroll
                 for (int it = 0; it < RP / RPI; ++it) {
@@ -475,6 +477,10 @@ bool plane_gemm_pipe_eligible(const GemmDesc &g)
     if (g.a_kmajor && g.a_rows_per_group() % pipe::BKS) return false;
     if (g.b_kmajor && g.b_rows_per_group() % pipe::BKS) return false;
     if (g.o_pg > 0 && g.o_pg % 32) return false;
+    // stacked problems: every problem's first stored row keeps those alignments
+    if (g.nb > 1 && ((g.a_kmajor && g.a_pg > 0 && g.Kl % pipe::BKS) || (g.b_kmajor && g.b_pg > 0 && g.Kl % pipe::BKS) ||
+                     (g.o_pg > 0 && g.Mi % 32)))
+        return false;
     // a clamped edge chunk must still lie inside the operand
     if (g.Mi < 8 || g.Nj < 8) return false;
     return g.Mi > 128 && g.Nj > 128;
@@ -511,7 +517,7 @@ static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *
         attr_set = true;
     }
     const int tiles_m = (g.Mi + 255) / 256, tiles_n = (g.Nj + 255) / 256;
-    const long total = (long)tiles_m * tiles_n * g.batch;
+    const long total = (long)tiles_m * tiles_n * g.batch * g.nb;
     if (total > 0x7fffffffL) return hipErrorInvalidValue;
     // one workgroup per CU that walks the block list (STL_GEMM_PERSIST=0: one block per workgroup)
     static const bool persist = []() { const char *e = getenv("STL_GEMM_PERSIST"); return !e || atoi(e) != 0; }();
@@ -523,7 +529,7 @@ static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *
     const int dbg = 0;
 #endif
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), smem, s, (const bf16_t *)A, (const bf16_t *)B, (TO *)Out, g.Mi, g.Nj,
-                       g.Kl, tiles_m, tiles_n, (int)total, dbg, g.a_rows_per_group(), g.b_rows_per_group(), g.o_rows_per_group());
+                       g.Kl, tiles_m, tiles_n, (int)total, dbg, g.a_rows_per_group(), g.b_rows_per_group(), g.o_rows_per_group(), g.batch);
     return hipGetLastError();
 }
 
@@ -534,6 +540,7 @@ static hipError_t launch_pipe_form(const GemmDesc &g, const void *A, const void 
         return g.accumulate ? launch_pipe_cfg<WAVES_M, WAVES_N, true, true, float, true>(g, A, B, Out, s)
                             : launch_pipe_cfg<WAVES_M, WAVES_N, true, true, float, false>(g, A, B, Out, s);
     }
+    if (g.a_kmajor) return launch_pipe_cfg<WAVES_M, WAVES_N, true, true, bf16_t, false>(g, A, B, Out, s);
     if (g.b_kmajor) return launch_pipe_cfg<WAVES_M, WAVES_N, false, true, bf16_t, false>(g, A, B, Out, s);
     return launch_pipe_cfg<WAVES_M, WAVES_N, false, false, bf16_t, false>(g, A, B, Out, s);
 }

@@ -46,7 +46,7 @@ bool recode_eligible(int dtype, int Cc);
 hipError_t launch_recode(const void *P, const void *Dm, const void *E2, void *Q, int R, int Cc, int r1, int r2, bool gelu,
                          int pg, hipStream_t s);
 
-// Batched plane products  Out[p][i][j] (+)= sum_l A[p](i,l) * B[p](l,j),  p < batch, dense planes.
+// Batched plane products  Out[b][p][i][j] (+)= sum_l A[b][p](i,l) * B[b][p](l,j),  p < batch, b < nb, dense planes.
 struct GemmDesc {
     int Mi, Nj, Kl;   // output rows, output columns, contraction length (all in tiles of the STL problem)
     int batch;        // number of planes r
@@ -57,9 +57,14 @@ struct GemmDesc {
     // layout of each operand: rows per group (see plane_row_base), counted in the operand's stored rows -- i for A
     // stored [i][l], l for A stored [l][i], and so on; 0 = plane-major
     int a_pg = 0, b_pg = 0, o_pg = 0;
-    int a_rows_per_group() const { return a_pg > 0 ? a_pg : (a_kmajor ? Kl : Mi); }
-    int b_rows_per_group() const { return b_pg > 0 ? b_pg : (b_kmajor ? Kl : Nj); }
-    int o_rows_per_group() const { return o_pg > 0 ? o_pg : Mi; }
+    // nb independent problems of this shape stacked along the stored rows of every operand: problem b owns stored rows
+    // [b * rows, (b + 1) * rows) of A, B and Out (rows = the operand's stored row count for one problem)
+    int nb = 1;
+    int a_rows() const { return a_kmajor ? Kl : Mi; }
+    int b_rows() const { return b_kmajor ? Kl : Nj; }
+    int a_rows_per_group() const { return a_pg > 0 ? a_pg : nb * a_rows(); }
+    int b_rows_per_group() const { return b_pg > 0 ? b_pg : nb * b_rows(); }
+    int o_rows_per_group() const { return o_pg > 0 ? o_pg : nb * Mi; }
 };
 hipError_t launch_plane_gemm(int dtype, const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s);
 // the slow any-shape path, also used directly for fp32 storage

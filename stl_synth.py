@@ -77,6 +77,24 @@ def stl_problem(m, k, n, r, seed, dtype="bf16", t=4, with_dC=False):
     return out
 
 
+def aa_problem(nbatch, m, k, n, r, seed, dtype="bf16", t=4, with_dC=False):
+    """Two stacked activation operands (attention-shaped products: nbatch = heads x images): A (nbatch*m, k) ~ N(0,1),
+    B (nbatch*k, n) ~ N(0, 1/k), three bases ~ N(0, 1/16).  Draw order: A, B, E_A, E_B, D, dC."""
+    if m % t or k % t or n % t:
+        raise ValueError("m, k, n must be divisible by t")
+    rng = np.random.default_rng(seed)
+    out = {
+        "A": _normal(rng, (nbatch * m, k), 1.0, dtype),
+        "B": _normal(rng, (nbatch * k, n), k ** -0.5, dtype),
+        "E_A": _normal(rng, (r, t * t), 0.25, dtype),
+        "E_B": _normal(rng, (r, t * t), 0.25, dtype),
+        "D": _normal(rng, (r, t * t), 0.25, dtype),
+    }
+    if with_dC:
+        out["dC"] = _normal(rng, (nbatch * m, n), 1.0, dtype)
+    return out
+
+
 def config_problem(name, r=None, with_dC=False):
     """Inputs of a named workload (optionally with another r for the sweep)."""
     c = dict(CONFIGS[name])

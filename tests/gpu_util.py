@@ -152,3 +152,41 @@ def encode_weight_backward(W, E_W, dWhat, dtype, accumulate=0, init=None, skip=(
                                    accumulate, ws, nbytes)
     torch.cuda.synchronize()
     return {"dW": host(dW), "dE_W": host(dE)}
+
+
+def aa_forward(A, B, E_A, E_B, D, nb, dtype, flags=0, save=False):
+    """Stacked two-activation STL through the C ABI.  Returns C (and Ahat, Bhat, Yhat, plane-major) as float64 numpy."""
+    m, k, n, r = A.shape[0] // nb, A.shape[1], B.shape[1], D.shape[0]
+    prob = stl.Problem(m, k, n, r, STL_DT[dtype])
+    Ad, Bd, Ea, Eb, Dd = (dev(x, dtype) for x in (A, B, E_A, E_B, D))
+    C = torch.full((nb * m, n), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
+    shapes = [(nb * m // 4, k // 4), (nb * k // 4, n // 4), (nb * m // 4, n // 4)]
+    bufs = [planes_buffer(r, R, Cc, dtype) for R, Cc in shapes] if save else [None] * 3
+    nbytes = stl.stl_aa_workspace_bytes(prob, nb, stl.STL_OP_FORWARD)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    stl.stl_aa_forward(prob, nb, Ad, Bd, Ea, Eb, Dd, C, bufs[0], bufs[1], bufs[2], ws, nbytes, flags)
+    torch.cuda.synchronize()
+    if save:
+        return (host(C),) + tuple(planes_to_host(b, r, R, Cc) for b, (R, Cc) in zip(bufs, shapes))
+    return host(C)
+
+
+def aa_backward(A, B, E_A, E_B, D, dC, nb, dtype, saved=None, accumulate=0, init=None, skip=()):
+    """Returns dict(dA, dB, dE_A, dE_B, dD) as float64 numpy.  saved: (Ahat, Bhat, Yhat) plane-major numpy or None."""
+    m, k, n, r = A.shape[0] // nb, A.shape[1], B.shape[1], D.shape[0]
+    prob = stl.Problem(m, k, n, r, STL_DT[dtype])
+    Ad, Bd, Ea, Eb, Dd, dCd = (dev(x, dtype) for x in (A, B, E_A, E_B, D, dC))
+    sv = [planes_to_dev(x, dtype) for x in saved] if saved is not None else [None] * 3
+    nan = float("nan")
+    outs = {"dA": torch.full((nb * m, k), nan, dtype=TORCH_DT[dtype], device="cuda"),
+            "dB": torch.full((nb * k, n), nan, dtype=TORCH_DT[dtype], device="cuda")}
+    for i, name in enumerate(("dE_A", "dE_B", "dD")):
+        outs[name] = (torch.full((r, 16), nan, dtype=torch.float32, device="cuda") if init is None
+                      else torch.from_numpy(np.asarray(init[i], dtype=np.float32)).cuda())
+    a = {k_: (None if k_ in skip else v) for k_, v in outs.items()}
+    nbytes = stl.stl_aa_workspace_bytes(prob, nb, stl.STL_OP_BACKWARD)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    stl.stl_aa_backward(prob, nb, Ad, Bd, Ea, Eb, Dd, dCd, sv[0], sv[1], sv[2], a["dA"], a["dB"], a["dE_A"], a["dE_B"],
+                        a["dD"], accumulate, ws, nbytes)
+    torch.cuda.synchronize()
+    return {k_: host(v) for k_, v in outs.items()}

@@ -220,6 +220,38 @@ stl_status_t stl_aa_backward(const stl_problem_t *prob, int64_t nbatch, const vo
                              void *dB, float *dE_A, float *dE_B, float *dD, int accumulate, void *ws,
                              size_t ws_bytes, void *stream);
 
+/*
+ * Row counts that t does not divide (Class-1 appendix, "More Details on STL Replacement in T2T-ViT", item 1):
+ * X is a stack of images with `rows` token rows each (197 in the paper), prob->m = nimg * rows real rows.  Every
+ * image is treated as extended with null rows to Mt = ceil(rows/4) tile rows (200 rows); the operator runs on the
+ * padded stack, and on the way back the 4 padded output rows of an image's last tile row are combined linearly
+ * into its nrho = rows mod 4 remaining real rows with the trainable coefficients `fold` (nrho x 4, fp32, row-major):
+ *     C[img*rows + 4(Mt-1) + rho][j] = sum_a fold[rho][a] * Ypad[img*4Mt + 4(Mt-1) + a][j].
+ * The paper's case is nrho = 1 (4 coefficients); one combination per remaining row is this library's reading for
+ * nrho = 2, 3.  Nothing is copied or padded in memory: null rows are read as zeros inside the encode, the fold is
+ * composed into the decoder of the last tile rows, and null rows are never written.  With rows % 4 == 0 the
+ * calls equal stl_forward / stl_backward and `fold`, `dfold` are ignored (may be NULL).
+ * X: m x k, C: m x n (real rows only).  Plane tensors are over the padded tile rows:
+ *   Xhat_save stl_plane_elems(nimg*Mt, K, r), Yhat_save stl_plane_elems(nimg*Mt, N, r) elements, or NULL.
+ * rows >= 4 and m % rows == 0 (INVALID_ARG otherwise).
+ * ws / ws_bytes: at least stl_ragged_workspace_bytes(prob, rows, STL_OP_FORWARD or STL_OP_BACKWARD).
+ */
+size_t stl_ragged_workspace_bytes(const stl_problem_t *prob, int64_t rows, int op);
+stl_status_t stl_ragged_forward(const stl_problem_t *prob, int64_t rows, const void *X, const void *What,
+                                const void *E_X, const void *D, const float *fold, void *C, void *Xhat_save,
+                                void *Yhat_save, void *ws, size_t ws_bytes, void *stream);
+/*
+ * Backward of <dC, C> for stl_ragged_forward: the outputs of stl_backward (gradients of null rows are dropped,
+ * null rows count as zeros in dE_X) and dfold (nrho x 4 fp32, or NULL):
+ *     dfold[rho][a] = sum_{img,j} dC[img*rows + 4(Mt-1) + rho][j] * Ypad[img*4Mt + 4(Mt-1) + a][j].
+ * accumulate applies to dWhat, dE_X, dD and dfold.
+ */
+stl_status_t stl_ragged_backward(const stl_problem_t *prob, int64_t rows, const void *X, const void *What,
+                                 const void *E_X, const void *D, const float *fold, const void *dC,
+                                 const void *Xhat_saved, const void *Yhat_saved, void *dX, float *dWhat,
+                                 float *dE_X, float *dD, float *dfold, int accumulate, void *ws,
+                                 size_t ws_bytes, void *stream);
+
 /* Static text for a status code. */
 const char *stl_status_string(stl_status_t status);
 /* Text of the last error raised on the calling thread ("" if none).  Thread-local storage. */

@@ -23,6 +23,7 @@ SYMBOLS = (
     "stl_plane_elems", "stl_workspace_bytes", "stl_encode_weight", "stl_encode_weight_backward", "stl_forward", "stl_backward", "stl_encode_activation",
     "stl_plane_matmul", "stl_decode", "stl_mlp_workspace_bytes", "stl_mlp_forward", "stl_recode",
     "stl_aa_workspace_bytes", "stl_aa_forward", "stl_aa_backward",
+    "stl_ragged_workspace_bytes", "stl_ragged_forward", "stl_ragged_backward",
     "stl_status_string", "stl_last_error", "stl_version",
 )
 
@@ -87,7 +88,11 @@ def _load():
     lib.stl_aa_workspace_bytes.argtypes = [pp, ctypes.c_int64, ctypes.c_int]
     lib.stl_aa_forward.argtypes = [pp, ctypes.c_int64] + [_P] * 10 + [ctypes.c_size_t, ctypes.c_int, _P]
     lib.stl_aa_backward.argtypes = [pp, ctypes.c_int64] + [_P] * 14 + [ctypes.c_int, _P, ctypes.c_size_t, _P]
-    for name in ("stl_aa_forward", "stl_aa_backward", "stl_encode_weight", "stl_forward", "stl_backward", "stl_encode_activation", "stl_plane_matmul",
+    lib.stl_ragged_workspace_bytes.restype = ctypes.c_size_t
+    lib.stl_ragged_workspace_bytes.argtypes = [pp, ctypes.c_int64, ctypes.c_int]
+    lib.stl_ragged_forward.argtypes = [pp, ctypes.c_int64] + [_P] * 9 + [ctypes.c_size_t, _P]
+    lib.stl_ragged_backward.argtypes = [pp, ctypes.c_int64] + [_P] * 13 + [ctypes.c_int, _P, ctypes.c_size_t, _P]
+    for name in ("stl_ragged_forward", "stl_ragged_backward", "stl_aa_forward", "stl_aa_backward", "stl_encode_weight", "stl_forward", "stl_backward", "stl_encode_activation", "stl_plane_matmul",
                  "stl_decode", "stl_mlp_forward", "stl_recode", "stl_encode_weight_backward"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stl_status_string.restype = ctypes.c_char_p
@@ -217,3 +222,20 @@ def stl_aa_backward(prob: Problem, nbatch: int, A, B, E_A, E_B, D, dC, Ahat_save
     _check(_load().stl_aa_backward(ctypes.byref(prob.c()), nbatch, _ptr(A), _ptr(B), _ptr(E_A), _ptr(E_B), _ptr(D), _ptr(dC),
                                    _ptr(Ahat_saved), _ptr(Bhat_saved), _ptr(Yhat_saved), _ptr(dA), _ptr(dB), _ptr(dE_A),
                                    _ptr(dE_B), _ptr(dD), accumulate, _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def stl_ragged_workspace_bytes(prob: Problem, rows: int, op: int) -> int:
+    return int(_load().stl_ragged_workspace_bytes(ctypes.byref(prob.c()), rows, op))
+
+
+def stl_ragged_forward(prob: Problem, rows: int, X, What, E_X, D, fold, C, Xhat_save=None, Yhat_save=None, ws=None,
+                       ws_bytes: int = 0, stream=None) -> None:
+    _check(_load().stl_ragged_forward(ctypes.byref(prob.c()), rows, _ptr(X), _ptr(What), _ptr(E_X), _ptr(D), _ptr(fold),
+                                      _ptr(C), _ptr(Xhat_save), _ptr(Yhat_save), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def stl_ragged_backward(prob: Problem, rows: int, X, What, E_X, D, fold, dC, Xhat_saved, Yhat_saved, dX, dWhat, dE_X, dD,
+                        dfold, accumulate: int = 0, ws=None, ws_bytes: int = 0, stream=None) -> None:
+    _check(_load().stl_ragged_backward(ctypes.byref(prob.c()), rows, _ptr(X), _ptr(What), _ptr(E_X), _ptr(D), _ptr(fold),
+                                       _ptr(dC), _ptr(Xhat_saved), _ptr(Yhat_saved), _ptr(dX), _ptr(dWhat), _ptr(dE_X),
+                                       _ptr(dD), _ptr(dfold), accumulate, _ptr(ws), ws_bytes, _stream(stream)))

@@ -252,6 +252,67 @@ stl_status_t check_batch(const stl_problem_t *p, const Dims &d, int64_t nb)
     return STL_OK;
 }
 
+// images of `rows` real rows each, padded with null rows to Mt tile rows (row counts the tile size does not divide)
+struct Ragged {
+    Dims d;            // of the padded problem: d.M = nimg * Mt tile rows
+    int Mt, rows, nimg, nrho;
+    stl::RowMap map(int sel) const
+    {
+        stl::RowMap rm;
+        if (nrho) { rm.Mt = Mt; rm.rows = rows; rm.sel = sel; }
+        return rm;
+    }
+};
+
+stl_status_t check_ragged(const stl_problem_t *p, int64_t rows, Ragged *g)
+{
+    if (!p) return fail(STL_ERR_INVALID_ARG, "problem descriptor is NULL");
+    if (rows < 4) return fail(STL_ERR_INVALID_ARG, "rows per image = %lld must be at least t = 4", (long long)rows);
+    if (p->m < rows || p->m % rows)
+        return fail(STL_ERR_INVALID_ARG, "m=%lld is not a multiple of the rows per image %lld", (long long)p->m, (long long)rows);
+    if (rows > kMaxDim || p->m > kMaxDim) return fail(STL_ERR_INVALID_ARG, "dimension larger than %lld", (long long)kMaxDim);
+    const int64_t nimg = p->m / rows, Mt = (rows + 3) / 4;
+    stl_problem_t padded = *p;
+    padded.m = nimg * Mt * 4;
+    stl_status_t st = check_problem(&padded, &g->d);
+    if (st != STL_OK) return st;
+    g->Mt = (int)Mt;
+    g->rows = (int)rows;
+    g->nimg = (int)nimg;
+    g->nrho = (int)(rows % 4);
+    return STL_OK;
+}
+
+struct RagWs {
+    size_t xhat, yhat, dyhat, dxhat, part, dprime, gtail, total;
+};
+
+RagWs ragged_layout(const Ragged &g, bool backward)
+{
+    const Dims &d = g.d;
+    RagWs w{};
+    size_t off = 0;
+    const size_t pk = align256((size_t)d.r * d.Mp() * d.K * d.es), pn = align256((size_t)d.r * d.Mp() * d.N * d.es);
+    w.xhat = off;
+    off += pk;
+    w.yhat = off;
+    off += pn;
+    if (backward) {
+        w.dyhat = off;
+        off += pn;
+        w.dxhat = off;
+        off += pk;
+        w.part = off;
+        off += align256(bwd_layout(d).total - bwd_layout(d).part);      // the same partial-sum area as stl_backward
+    }
+    w.dprime = off;
+    off += align256((size_t)d.r * 16 * sizeof(float));
+    w.gtail = off;
+    off += align256((size_t)d.r * 16 * sizeof(float));
+    w.total = off;
+    return w;
+}
+
 #define STL_HIP(call, what)                                \
     do {                                                   \
         hipError_t e__ = (call);                           \
@@ -687,6 +748,127 @@ stl_status_t stl_aa_backward(const stl_problem_t *prob, int64_t nbatch, const vo
             if (dB) STL_HIP(stl::launch_decode(dt, dbhat, E_B, dB, RB, d.N, d.r, false, PG, s), "aa_backward/decode dB");
             if (dE_B) STL_HIP(stl::launch_outer_reduce(dt, dbhat, B, dE_B, part, RB, d.N, d.r, accumulate, PG, s), "aa_backward/dE_B");
         }
+    }
+    return STL_OK;
+}
+
+size_t stl_ragged_workspace_bytes(const stl_problem_t *prob, int64_t rows, int op)
+{
+    Ragged g;
+    if (check_ragged(prob, rows, &g) != STL_OK) return 0;
+    if (op == STL_OP_FORWARD) return ragged_layout(g, false).total;
+    if (op == STL_OP_BACKWARD) return ragged_layout(g, true).total;
+    fail(STL_ERR_INVALID_ARG, "stl_ragged_workspace_bytes: op must be STL_OP_FORWARD or STL_OP_BACKWARD");
+    return 0;
+}
+
+stl_status_t stl_ragged_forward(const stl_problem_t *prob, int64_t rows, const void *X, const void *What, const void *E_X,
+                                const void *D, const float *fold, void *C, void *Xhat_save, void *Yhat_save, void *ws,
+                                size_t ws_bytes, void *stream)
+{
+    Ragged g;
+    stl_status_t st = check_ragged(prob, rows, &g);
+    if (st != STL_OK) return st;
+    const Dims &d = g.d;
+    if (!X || !What || !E_X || !D || !C) return fail(STL_ERR_INVALID_ARG, "stl_ragged_forward: NULL pointer");
+    if (g.nrho && !fold) return fail(STL_ERR_INVALID_ARG, "stl_ragged_forward: fold coefficients are NULL");
+    if (any_misaligned(X, What, E_X, D, fold, C, Xhat_save, Yhat_save))
+        return fail(STL_ERR_INVALID_ARG, "stl_ragged_forward: pointer not 16-byte aligned");
+    const RagWs w = ragged_layout(g, false);
+    if (!ws || ws_bytes < w.total)
+        return fail(STL_ERR_WORKSPACE, "stl_ragged_forward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
+    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_ragged_forward: workspace is not 16-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    const int dt = prob->dtype;
+    char *base = (char *)ws;
+    void *xhat = Xhat_save ? Xhat_save : (void *)(base + w.xhat);
+    void *yhat = Yhat_save ? Yhat_save : (void *)(base + w.yhat);
+    float *dprime = (float *)(base + w.dprime);
+    // null rows are read as zeros by the encode; rows of complete tile rows are decoded with D, each image's last tile
+    // row with the fold composed into the decoder
+    STL_HIP(stl::launch_encode(dt, X, E_X, xhat, d.M, d.K, d.r, PG, s, g.map(0)), "ragged_forward/encode");
+    stl::GemmDesc gd{d.M, d.N, d.K, d.r, false, true, false, false, PG, 0, PG};
+    STL_HIP(stl::launch_plane_gemm(dt, gd, xhat, What, yhat, s), "ragged_forward/plane products");
+    if (!g.nrho) {
+        STL_HIP(stl::launch_decode(dt, yhat, D, C, d.M, d.N, d.r, false, PG, s), "ragged_forward/decode");
+        return STL_OK;
+    }
+    STL_HIP(stl::launch_fold_decoder(dt, D, fold, dprime, d.r, g.nrho, s), "ragged_forward/compose fold");
+    STL_HIP(stl::launch_decode(dt, yhat, D, C, d.M, d.N, d.r, false, PG, s, g.map(1)), "ragged_forward/decode");
+    STL_HIP(stl::launch_decode(dt, yhat, dprime, C, d.M, d.N, d.r, false, PG, s, g.map(2), true), "ragged_forward/decode + fold");
+    return STL_OK;
+}
+
+stl_status_t stl_ragged_backward(const stl_problem_t *prob, int64_t rows, const void *X, const void *What, const void *E_X,
+                                 const void *D, const float *fold, const void *dC, const void *Xhat_saved,
+                                 const void *Yhat_saved, void *dX, float *dWhat, float *dE_X, float *dD, float *dfold,
+                                 int accumulate, void *ws, size_t ws_bytes, void *stream)
+{
+    Ragged g;
+    stl_status_t st = check_ragged(prob, rows, &g);
+    if (st != STL_OK) return st;
+    const Dims &d = g.d;
+    if (!X || !What || !E_X || !D || !dC) return fail(STL_ERR_INVALID_ARG, "stl_ragged_backward: NULL input pointer");
+    if (g.nrho && !fold) return fail(STL_ERR_INVALID_ARG, "stl_ragged_backward: fold coefficients are NULL");
+    if (any_misaligned(X, What, E_X, D, fold, dC, Xhat_saved, Yhat_saved, dX, dWhat, dE_X, dD, dfold))
+        return fail(STL_ERR_INVALID_ARG, "stl_ragged_backward: pointer not 16-byte aligned");
+    if (accumulate != 0 && accumulate != 1) return fail(STL_ERR_INVALID_ARG, "stl_ragged_backward: accumulate must be 0 or 1");
+    const RagWs w = ragged_layout(g, true);
+    if (!ws || ws_bytes < w.total)
+        return fail(STL_ERR_WORKSPACE, "stl_ragged_backward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
+    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_ragged_backward: workspace is not 16-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    const int dt = prob->dtype;
+    char *base = (char *)ws;
+    const void *xhat = Xhat_saved ? Xhat_saved : (const void *)(base + w.xhat);
+    void *dyhat = base + w.dyhat, *dxhat = base + w.dxhat;
+    float *part = (float *)(base + w.part), *dprime = (float *)(base + w.dprime), *gtail = (float *)(base + w.gtail);
+    const bool want_fold = g.nrho && dfold;
+    const bool need_yhat = dD || want_fold;
+
+    if ((dWhat || (need_yhat && !Yhat_saved)) && !Xhat_saved)
+        STL_HIP(stl::launch_encode(dt, X, E_X, base + w.xhat, d.M, d.K, d.r, PG, s, g.map(0)), "ragged_backward/encode X");
+    const void *yhat = Yhat_saved;
+    if (need_yhat && !yhat) {
+        stl::GemmDesc gd{d.M, d.N, d.K, d.r, false, true, false, false, PG, 0, PG};
+        STL_HIP(stl::launch_plane_gemm(dt, gd, xhat, What, base + w.yhat, s), "ragged_backward/recompute Yhat");
+        yhat = base + w.yhat;
+    }
+    // dYhat and dD from the complete tile rows (all of them when nothing is ragged) ...
+    const stl::RowMap body = g.map(1);
+    if (dD && stl::encode_outer_eligible(dt, d.N)) {
+        STL_HIP(stl::launch_encode_outer(dC, D, dyhat, yhat, dD, part, d.M, d.N, d.r, accumulate, PG, s, body), "ragged_backward/dYhat + dD");
+    } else {
+        STL_HIP(stl::launch_encode(dt, dC, D, dyhat, d.M, d.N, d.r, PG, s, body), "ragged_backward/encode dC");
+        if (dD) STL_HIP(stl::launch_outer_reduce(dt, yhat, dC, dD, part, d.M, d.N, d.r, accumulate, PG, s, body), "ragged_backward/dD");
+    }
+    if (g.nrho) {
+        // ... and from each image's last tile row through the fold: its adjoint is an encode with the composed decoder;
+        // one product Yhat (x) dC over those tile rows feeds both dD and dfold
+        const stl::RowMap tail = g.map(2);
+        STL_HIP(stl::launch_fold_decoder(dt, D, fold, dprime, d.r, g.nrho, s), "ragged_backward/compose fold");
+        STL_HIP(stl::launch_encode(dt, dC, dprime, dyhat, d.M, d.N, d.r, PG, s, tail, true), "ragged_backward/encode folded dC");
+        if (dD || want_fold) {
+            STL_HIP(stl::launch_outer_reduce(dt, yhat, dC, gtail, part, d.M, d.N, d.r, 0, PG, s, tail), "ragged_backward/last tile rows");
+            STL_HIP(stl::launch_fold_grads(dt, gtail, D, fold, dD, dfold, d.r, g.nrho, accumulate, s), "ragged_backward/dD + dfold");
+        }
+    }
+    if (dX || dE_X) {
+        stl::GemmDesc gd{d.M, d.K, d.N, d.r, false, false, false, false, PG, 0, PG};
+        STL_HIP(stl::launch_plane_gemm(dt, gd, dyhat, What, dxhat, s), "ragged_backward/dXhat");
+    }
+    if (dWhat) {
+        stl::GemmDesc gd{d.K, d.N, d.M, d.r, true, true, true, accumulate != 0, PG, PG, 0};
+        STL_HIP(stl::launch_plane_gemm(dt, gd, xhat, dyhat, dWhat, s), "ragged_backward/dWhat");
+    }
+    // gradients of null rows are dropped (never written); null rows of X count as zeros in dE_X
+    const stl::RowMap all = g.map(0);
+    if (dX && dE_X && stl::decode_outer_eligible(dt, d.K)) {
+        STL_HIP(stl::launch_decode_outer(dxhat, E_X, dX, X, dE_X, part, d.M, d.K, d.r, accumulate, PG, s, all), "ragged_backward/dX + dE_X");
+    } else {
+        if (dX) STL_HIP(stl::launch_decode(dt, dxhat, E_X, dX, d.M, d.K, d.r, false, PG, s, all), "ragged_backward/decode dX");
+        if (dE_X)
+            STL_HIP(stl::launch_outer_reduce(dt, dxhat, X, dE_X, part, d.M, d.K, d.r, accumulate, PG, s, all), "ragged_backward/dE_X");
     }
     return STL_OK;
 }

@@ -27,7 +27,8 @@ typedef short v4i16_t __attribute__((ext_vector_type(4)));
 template <int KC>   // KC = number of 32-plane groups (1: r <= 32, 2: r <= 64)
 __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ E,
                                                              bf16_t *__restrict__ P, const bf16_t *__restrict__ Qp,
-                                                             float *__restrict__ part, int R, int Cc, int r, int chunks, int pg)
+                                                             float *__restrict__ part, int R, int Cc, int r, int chunks, int pg,
+                                                             RowMap rm)
 {
     constexpr int ROWB = 128;                               // bytes per plane row of the slab (64 tiles)
     __shared__ __align__(16) char sT_all[4][64 * 32];       // per wavefront: [tile][16 entries] bf16
@@ -74,11 +75,14 @@ __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__res
     u32x4_t qa[KC * 4];     // plane segments, loader role: plane 8*g8 + pr, tiles 8ch .. 8ch+7
     auto fetch = [&](int Ii, int cki) {
         const int J0 = cki * 64;
-        const size_t rowb = Ii < R ? plane_row_base(Ii, pg, r, Cc) : 0;
+        const int Ia = Ii < R ? rm.tile_row(Ii) : 0;        // Ii counts the tile rows of this launch, Ia is the tile row itself
+        const size_t rowb = plane_row_base(Ia, pg, r, Cc);
+        const bool row_ok = Ii < R && kq < rm.valid(Ia);    // a null row reads as zero
+        const size_t r0 = rm.row0(Ia);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             u32x2_t v = {0u, 0u};
-            if (Ii < R && J0 + trel[u] < Cc) v = *reinterpret_cast<const u32x2_t *>(A + ((size_t)Ii * 4 + kq) * ld + (size_t)(J0 + trel[u]) * 4);
+            if (row_ok && J0 + trel[u] < Cc) v = *reinterpret_cast<const u32x2_t *>(A + (r0 + kq) * ld + (size_t)(J0 + trel[u]) * 4);
             xa[u] = v;
         }
 #pragma unroll
@@ -92,7 +96,7 @@ __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__res
     fetch(In, ckn);
 
     for (long item0 = (long)blockIdx.x * 4; item0 < items; item0 += stride) {
-        const int I = In, J0 = ckn * 64;
+        const int Iidx = In, J0 = ckn * 64;
         u32x2_t x[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) x[u] = xa[u];
@@ -106,7 +110,8 @@ __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__res
         ckn += dck;
         if (ckn >= chunks) { ckn -= chunks; ++In; }
         if (item0 + stride < items) fetch(In, ckn);
-        if (I >= R) continue;
+        if (Iidx >= R) continue;
+        const int I = rm.tile_row(Iidx);
 
         // tile rows -> second slab
 #pragma unroll
@@ -192,17 +197,19 @@ int encode_outer_blocks(int R, int Cc)
 }
 
 hipError_t launch_encode_outer(const void *A, const void *E, void *P, const void *Qp, float *G, float *part, int R, int Cc,
-                               int r, int accumulate, int pg, hipStream_t s)
+                               int r, int accumulate, int pg, hipStream_t s, RowMap rm)
 {
     if (pg <= 0) pg = R;
+    R = rm.count(R);                                        // tile rows this launch walks over
+    if (R <= 0) return hipErrorInvalidValue;
     const int chunks = (Cc + 63) / 64;
     const int nb = encode_outer_blocks(R, Cc);
     if (r <= 32)
         hipLaunchKernelGGL(encode_outer16_kernel<1>, dim3(nb), dim3(256), 0, s, (const bf16_t *)A, (const bf16_t *)E,
-                           (bf16_t *)P, (const bf16_t *)Qp, part, R, Cc, r, chunks, pg);
+                           (bf16_t *)P, (const bf16_t *)Qp, part, R, Cc, r, chunks, pg, rm);
     else
         hipLaunchKernelGGL(encode_outer16_kernel<2>, dim3(nb), dim3(256), 0, s, (const bf16_t *)A, (const bf16_t *)E,
-                           (bf16_t *)P, (const bf16_t *)Qp, part, R, Cc, r, chunks, pg);
+                           (bf16_t *)P, (const bf16_t *)Qp, part, R, Cc, r, chunks, pg, rm);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_outer_final(part, G, nb, r * 16, accumulate, s);

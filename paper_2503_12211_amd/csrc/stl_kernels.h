@@ -9,23 +9,63 @@ namespace stl {
 // pg: rows per group of the plane tensor's layout (see plane_row_base); 0 = plane-major (one group of all rows)
 constexpr int kPlaneGroup = 64;   // group size of the activation-side plane tensors
 
+// Which matrix rows lie behind a tile row of the plane tensors.
+//   plain  (Mt == 0): tile row I covers matrix rows 4I .. 4I+3.
+//   ragged (Mt > 0):  the matrix is a stack of images with `rows` real rows each (197 tokens in the Class-1 appendix),
+//     thought of as padded with null rows to Mt = ceil(rows / 4) tile rows per image.  Tile row I = img * Mt + l covers
+//     matrix rows img * rows + 4l + a for the a with 4l + a < rows; the other entry rows are null rows: they read as
+//     zero and are never written.  Only the last tile row of an image can be incomplete.
+// A launch walks over a selection of the tile rows: all of them, only the complete-by-position ones (every tile row
+// but the last of each image), or only the last of each image.
+struct RowMap {
+    int Mt = 0, rows = 0;
+    int sel = 0;                       // 0: all tile rows, 1: all but each image's last, 2: each image's last
+    __host__ __device__ __forceinline__ int tile_row(int idx) const
+    {
+        if (Mt == 0 || sel == 0) return idx;
+        if (sel == 1) return idx + idx / (Mt - 1);
+        return idx * Mt + Mt - 1;
+    }
+    __host__ __device__ __forceinline__ size_t row0(int I) const
+    {
+        if (Mt == 0) return (size_t)I * 4;
+        const int img = I / Mt;
+        return (size_t)img * rows + (size_t)(I - img * Mt) * 4;
+    }
+    __host__ __device__ __forceinline__ int valid(int I) const       // real entry rows of tile row I (1..4)
+    {
+        if (Mt == 0) return 4;
+        const int left = rows - (I % Mt) * 4;
+        return left < 4 ? left : 4;
+    }
+    // number of tile rows a launch with this selection walks over, R = all tile rows
+    __host__ __device__ __forceinline__ int count(int R) const
+    {
+        if (Mt == 0 || sel == 0) return R;
+        return sel == 1 ? R / Mt * (Mt - 1) : R / Mt;
+    }
+};
+
 // planes P[p][R][Cc] <- encoder E (r x 16) applied to every 4x4 tile of A (4R x 4Cc)
-hipError_t launch_encode(int dtype, const void *A, const void *E, void *P, int R, int Cc, int r, int pg, hipStream_t s);
+// rm: which matrix rows lie behind the tile rows, and which tile rows the launch walks over (R always counts ALL tile
+// rows of the plane tensor); basis_f32: E (or Dm) is stored as fp32 whatever the dtype
+hipError_t launch_encode(int dtype, const void *A, const void *E, void *P, int R, int Cc, int r, int pg, hipStream_t s,
+                         RowMap rm = RowMap(), bool basis_f32 = false);
 // matrix Cmat (4R x 4Cc) <- decoder Dm^T (r x 16 stored) applied to planes P[p][R][Cc]
 hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, int R, int Cc, int r, bool gelu, int pg,
-                         hipStream_t s);
+                         hipStream_t s, RowMap rm = RowMap(), bool basis_f32 = false);
 
 // G[p][q] (+)= sum_tiles P[p][tile] * tileview(V)[tile][q]; `part` holds outer_reduce_blocks(R*Cc) * r * 16 floats
 int outer_reduce_blocks(int64_t tiles);
 hipError_t launch_outer_reduce(int dtype, const void *P, const void *V, float *G, float *part, int R, int Cc, int r,
-                               int accumulate, int pg, hipStream_t s);
+                               int accumulate, int pg, hipStream_t s, RowMap rm = RowMap());
 
 // decode and basis gradient in one pass over the planes (bf16): Cmat <- decode(P, Dm), G (+)= P . tileview(V);
 // `part` holds decode_outer_blocks(R, Cc) * r * 16 floats
 bool decode_outer_eligible(int dtype, int Cc);
 int decode_outer_blocks(int R, int Cc);
 hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const void *V, float *G, float *part, int R,
-                               int Cc, int r, int accumulate, int pg, hipStream_t s);
+                               int Cc, int r, int accumulate, int pg, hipStream_t s, RowMap rm = RowMap());
 
 // G[i] (+)= sum over nb partials part[b][i], i < n_out, in block order (second stage of the basis-gradient sums)
 hipError_t launch_outer_final(const float *part, float *G, int nb, int n_out, int accumulate, hipStream_t s);
@@ -35,7 +75,13 @@ hipError_t launch_outer_final(const float *part, float *G, int nb, int n_out, in
 bool encode_outer_eligible(int dtype, int Cc);
 int encode_outer_blocks(int R, int Cc);
 hipError_t launch_encode_outer(const void *A, const void *E, void *P, const void *Qp, float *G, float *part, int R, int Cc,
-                               int r, int accumulate, int pg, hipStream_t s);
+                               int r, int accumulate, int pg, hipStream_t s, RowMap rm = RowMap());
+
+// fold of an image's last tile row (row counts not divisible by 4): composed decoder Dp (r x 16 fp32) from Dm and the
+// nrho x 4 fold coefficients; and the gradients that come from those tile rows, given Gt = Yhat (x) dC over them
+hipError_t launch_fold_decoder(int dtype, const void *Dm, const float *fold, float *Dp, int r, int nrho, hipStream_t s);
+hipError_t launch_fold_grads(int dtype, const float *Gt, const void *Dm, const float *fold, float *dD, float *dfold, int r,
+                             int nrho, int accumulate, hipStream_t s);
 
 // out[i] = bf16(in[i]), round to nearest even
 hipError_t launch_cast_bf16(const float *in, void *out, size_t n, hipStream_t s);

@@ -11,25 +11,29 @@ namespace stl {
 // One thread per tile; lanes run along L so that every row segment and every plane row is
 // read / written contiguously by a wavefront.
 // ---------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(256) void encode_kernel(const T *__restrict__ A, const T *__restrict__ E,
-                                                     T *__restrict__ P, int R, int Cc, int r, int pg)
+// TB: type the basis is stored in (the storage type, or fp32 for a basis composed on the device).  R counts the tile
+// rows this launch walks over (see RowMap).
+template <typename T, typename TB>
+__global__ __launch_bounds__(256) void encode_kernel(const T *__restrict__ A, const TB *__restrict__ E,
+                                                     T *__restrict__ P, int R, int Cc, int r, int pg, RowMap rm)
 {
     __shared__ float sE[64 * 16];
     const int tid = threadIdx.y * blockDim.x + threadIdx.x;
-    for (int i = tid; i < r * 16; i += 256) sE[i] = Elem<T>::ld(E + i);
+    for (int i = tid; i < r * 16; i += 256) sE[i] = Elem<TB>::ld(E + i);
     __syncthreads();
 
     const int L = blockIdx.x * blockDim.x + threadIdx.x;
-    const int I = blockIdx.y * blockDim.y + threadIdx.y;
-    if (L >= Cc || I >= R) return;
+    const int idx = blockIdx.y * blockDim.y + threadIdx.y;
+    if (L >= Cc || idx >= R) return;
+    const int I = rm.tile_row(idx), nv = rm.valid(I);
+    const size_t r0 = rm.row0(I);
 
     const size_t ld = (size_t)Cc * 4;
     float x[16];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) x[a * 4 + b] = Elem<T>::ld(A + ((size_t)I * 4 + a) * ld + (size_t)L * 4 + b);
+        for (int b = 0; b < 4; ++b) x[a * 4 + b] = a < nv ? Elem<T>::ld(A + (r0 + a) * ld + (size_t)L * 4 + b) : 0.f;
 
     const size_t plane = (size_t)pg * Cc;
     T *out = P + plane_row_base(I, pg, r, Cc) + L;
@@ -44,18 +48,20 @@ __global__ __launch_bounds__(256) void encode_kernel(const T *__restrict__ A, co
 // ---------------------------------------------------------------------------------------
 // decode:  Cmat[4I + q/4][4J + q%4] = sum_p Dm[p][q] * P[p][I][J]     (+ optional GELU)
 // ---------------------------------------------------------------------------------------
-template <typename T, bool GELU>
-__global__ __launch_bounds__(256) void decode_kernel(const T *__restrict__ P, const T *__restrict__ Dm,
-                                                     T *__restrict__ Cmat, int R, int Cc, int r, int pg)
+template <typename T, typename TB, bool GELU>
+__global__ __launch_bounds__(256) void decode_kernel(const T *__restrict__ P, const TB *__restrict__ Dm,
+                                                     T *__restrict__ Cmat, int R, int Cc, int r, int pg, RowMap rm)
 {
     __shared__ float sD[64 * 16];
     const int tid = threadIdx.y * blockDim.x + threadIdx.x;
-    for (int i = tid; i < r * 16; i += 256) sD[i] = Elem<T>::ld(Dm + i);
+    for (int i = tid; i < r * 16; i += 256) sD[i] = Elem<TB>::ld(Dm + i);
     __syncthreads();
 
     const int J = blockIdx.x * blockDim.x + threadIdx.x;
-    const int I = blockIdx.y * blockDim.y + threadIdx.y;
-    if (J >= Cc || I >= R) return;
+    const int idx = blockIdx.y * blockDim.y + threadIdx.y;
+    if (J >= Cc || idx >= R) return;
+    const int I = rm.tile_row(idx), nv = rm.valid(I);
+    const size_t r0 = rm.row0(I);
 
     const size_t plane = (size_t)pg * Cc;
     const T *in = P + plane_row_base(I, pg, r, Cc) + J;
@@ -74,7 +80,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const T *__restrict__ P, co
         for (int b = 0; b < 4; ++b) {
             float v = c[a * 4 + b];
             if (GELU) v = gelu_erf(v);
-            Elem<T>::st(Cmat + ((size_t)I * 4 + a) * ld + (size_t)J * 4 + b, v);
+            if (a < nv) Elem<T>::st(Cmat + (r0 + a) * ld + (size_t)J * 4 + b, v);
         }
 }
 
@@ -87,7 +93,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const T *__restrict__ P, co
 template <typename T>
 __global__ __launch_bounds__(256) void outer_partial_kernel(const T *__restrict__ P, const T *__restrict__ V,
                                                             float *__restrict__ part, int R, int Cc, int r,
-                                                            int tiles_per_block, int pg)
+                                                            int tiles_per_block, int pg, RowMap rm)
 {
     // 256 threads: q = tid & 15, tile lane = tid >> 4 (16 tiles in flight); loop over planes.
     __shared__ float red[16][16];
@@ -100,9 +106,10 @@ __global__ __launch_bounds__(256) void outer_partial_kernel(const T *__restrict_
     for (int p = 0; p < r; ++p) {
         float s = 0.f;
         for (size_t tile = t0 + tl; tile < t1; tile += 16) {
-            const size_t I = tile / Cc, J = tile % Cc;
-            const float v = Elem<T>::ld(V + (I * 4 + (q >> 2)) * ld + J * 4 + (q & 3));
-            const float y = Elem<T>::ld(P + plane_row_base((int)I, pg, r, Cc) + (size_t)p * pg * Cc + J);
+            const size_t J = tile % Cc;
+            const int I = rm.tile_row((int)(tile / Cc));
+            const float v = (q >> 2) < rm.valid(I) ? Elem<T>::ld(V + (rm.row0(I) + (q >> 2)) * ld + J * 4 + (q & 3)) : 0.f;
+            const float y = Elem<T>::ld(P + plane_row_base(I, pg, r, Cc) + (size_t)p * pg * Cc + J);
             s = fmaf(y, v, s);
         }
         red[tl][q] = s;
@@ -148,12 +155,15 @@ __global__ __launch_bounds__(256) void outer_final_kernel(const float *__restric
 // holds 4 consecutive tiles of a plane and writes them with one 8-byte store.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void encode_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ E,
-                                                          bf16_t *__restrict__ P, int R, int Cc, int r, int chunks, int pg)
+                                                          bf16_t *__restrict__ P, int R, int Cc, int r, int chunks, int pg,
+                                                          RowMap rm)
 {
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long item = (long)blockIdx.x * 4 + wave;          // (tile row, chunk of 128 tile columns)
     if (item >= (long)R * chunks) return;
-    const int I = (int)(item / chunks), J0 = (int)(item % chunks) * 128;
+    const int I = rm.tile_row((int)(item / chunks)), J0 = (int)(item % chunks) * 128;
+    const int nv = rm.valid(I);
+    const size_t r0 = rm.row0(I);
     const int j = lane & 31, h = lane >> 5;
     const size_t ld = (size_t)Cc * 4;
     const int Jl = J0 + 4 * j;                               // first of this lane's 4 tiles
@@ -164,8 +174,8 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(const bf16_t *__restri
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             u32x4_t z = {0u, 0u, 0u, 0u};
-            if (Jl + 2 * c < Cc)
-                z = *reinterpret_cast<const u32x4_t *>(A + ((size_t)I * 4 + 2 * h + a) * ld + (size_t)(Jl + 2 * c) * 4);
+            if (Jl + 2 * c < Cc && 2 * h + a < nv)
+                z = *reinterpret_cast<const u32x4_t *>(A + (r0 + 2 * h + a) * ld + (size_t)(Jl + 2 * c) * 4);
             row[a][c] = z;
         }
 
@@ -207,7 +217,7 @@ __global__ __launch_bounds__(256) void encode_mfma_kernel(const bf16_t *__restri
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restrict__ P, const bf16_t *__restrict__ V,
                                                          float *__restrict__ part, int R, int Cc, int r,
-                                                         int tiles_per_block, int pg)
+                                                         int tiles_per_block, int pg, RowMap rm)
 {
     constexpr int PITCH = 64 + 8;                       // bf16 elements per LDS row (16-byte aligned rows)
     __shared__ __align__(16) bf16_t sV[4][16][PITCH];
@@ -234,9 +244,12 @@ __global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restric
         const long tb = base + wave * 64;
         const long tile = tb + lane;
         if (tile < t1) {
-            const long I = tile / Cc, J = tile - I * Cc;
+            const long idx = tile / Cc, J = tile - idx * Cc;
+            const int I = rm.tile_row((int)idx), nv = rm.valid(I);
+            const size_t r0 = rm.row0(I);
 #pragma unroll
-            for (int a = 0; a < 4; ++a) v[a] = *reinterpret_cast<const u32x2_t *>(V + ((size_t)I * 4 + a) * ld + (size_t)J * 4);
+            for (int a = 0; a < 4; ++a)
+                v[a] = a < nv ? *reinterpret_cast<const u32x2_t *>(V + (r0 + a) * ld + (size_t)J * 4) : u32x2_t{0u, 0u};
         } else {
 #pragma unroll
             for (int a = 0; a < 4; ++a) v[a] = u32x2_t{0u, 0u};
@@ -245,7 +258,7 @@ __global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restric
         for (int s = 0; s < 2; ++s) {
             const long tk = tb + 32 * s + 8 * kq;        // 8 consecutive tiles of one tile row (Cc % 8 == 0): all in or all out
             const int Ik = (int)(tk / Cc);
-            const size_t off = tk < t1 ? plane_row_base(Ik, pg, r, Cc) + (size_t)(tk - (long)Ik * Cc) : 0;
+            const size_t off = tk < t1 ? plane_row_base(rm.tile_row(Ik), pg, r, Cc) + (size_t)(tk - (long)Ik * Cc) : 0;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int pl = 16 * g + q;
@@ -308,7 +321,8 @@ typedef short v4i16_t __attribute__((ext_vector_type(4)));
 template <bool GELU, int KC, bool OUTER>   // KC = number of 32-plane groups (1: r <= 32, 2: r <= 64)
 __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restrict__ P, const bf16_t *__restrict__ Dm,
                                                           bf16_t *__restrict__ Cmat, int R, int Cc, int r, int chunks,
-                                                          const bf16_t *__restrict__ V, float *__restrict__ part, int pg)
+                                                          const bf16_t *__restrict__ V, float *__restrict__ part, int pg,
+                                                          RowMap rm)
 {
     constexpr int ROWB = 128;                               // bytes per LDS row (64 tiles)
     constexpr int VPITCH = 64 + 8;                          // bf16 elements per row of the entry x tile staging
@@ -355,7 +369,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
     u32x2_t xpre[OUTER ? 4 : 1];
     auto fetch = [&](int Ii, int cki) {
         const int Jl = cki * 64 + 8 * ch;
-        const size_t rowb = Ii < R ? plane_row_base(Ii, pg, r, Cc) : 0;
+        const int Ia = Ii < R ? rm.tile_row(Ii) : 0;        // Ii counts the tile rows of this launch, Ia is the tile row itself
+        const size_t rowb = plane_row_base(Ia, pg, r, Cc);
 #pragma unroll
         for (int g8 = 0; g8 < KC * 4; ++g8) {
             const int pl = 8 * g8 + pr;
@@ -364,11 +379,12 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
             pre[g8] = v;
         }
         if (OUTER) {
-            const int Jt = cki * 64 + lane;
+            const int Jt = cki * 64 + lane, nv = rm.valid(Ia);
+            const size_t r0 = rm.row0(Ia);
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
                 u32x2_t xv = {0u, 0u};
-                if (Ii < R && Jt < Cc) xv = *reinterpret_cast<const u32x2_t *>(V + ((size_t)Ii * 4 + a) * ld + (size_t)Jt * 4);
+                if (Ii < R && Jt < Cc && a < nv) xv = *reinterpret_cast<const u32x2_t *>(V + (r0 + a) * ld + (size_t)Jt * 4);
                 xpre[a] = xv;
             }
         }
@@ -376,8 +392,9 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
     fetch(In, ckn);
 
     for (long item0 = (long)blockIdx.x * 4; item0 < items; item0 += stride) {
-        const int I = In, J0 = ckn * 64;
-        const bool live = I < R;
+        const int J0 = ckn * 64;
+        const bool live = In < R;
+        const int I = live ? rm.tile_row(In) : 0;
         // slab and sV belong to this wavefront alone and its LDS operations execute in order: the writes below land
         // after the previous round's fragment reads without a workgroup barrier (which would also make the wavefront
         // wait for the loads it is about to put in flight)
@@ -418,6 +435,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
             }
         }
         if (live) {
+            const int nv_out = rm.valid(I);
+            const size_t r0_out = rm.row0(I);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {                   // 16 tiles per MFMA
                 f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
@@ -438,11 +457,11 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
                 }
                 // lane holds row a = kq of tile J0 + 16u + j: entries acc[0..3]
                 const int J = J0 + 16 * u + j;
-                if (J < Cc) {
+                if (J < Cc && kq < nv_out) {
                     float c0 = acc[0], c1 = acc[1], c2 = acc[2], c3 = acc[3];
                     if (GELU) { c0 = gelu_erf(c0); c1 = gelu_erf(c1); c2 = gelu_erf(c2); c3 = gelu_erf(c3); }
                     const u32x2_t w = {pack_bf16x2(c0, c1), pack_bf16x2(c2, c3)};
-                    *reinterpret_cast<u32x2_t *>(Cmat + ((size_t)I * 4 + kq) * ld + (size_t)J * 4) = w;
+                    *reinterpret_cast<u32x2_t *>(Cmat + (r0_out + kq) * ld + (size_t)J * 4) = w;
                 }
             }
         }
@@ -459,6 +478,72 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
         for (int i = threadIdx.x; i < r * 16; i += 256)
             part[(size_t)blockIdx.x * r * 16 + i] = ((red[i] + red[1024 + i]) + red[2048 + i]) + red[3072 + i];
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Images whose row count the tile size does not divide (Class-1 appendix, "More Details on STL Replacement in
+// T2T-ViT", item 1): the nrho = rows mod 4 real rows of an image's last tile row are linear combinations of the 4
+// padded output rows, out[rho] = sum_a fold[rho][a] y[a].  Since y[a][c] = sum_p Dm[p][4a+c] yhat[p], the fold is a
+// decode with the composed decoder
+//     Dp[p][4 rho + c] = sum_a fold[rho][a] Dm[p][4a + c]      (zero for rho >= nrho),
+// and its adjoint an encode with the same Dp.  Dp is kept in fp32.
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void fold_decoder_kernel(const T *__restrict__ Dm, const float *__restrict__ fold,
+                                                           float *__restrict__ Dp, int r, int nrho)
+{
+    for (int i = threadIdx.x; i < r * 16; i += 256) {
+        const int p = i >> 4, rho = (i >> 2) & 3, c = i & 3;
+        float s = 0.f;
+        if (rho < nrho)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) s = fmaf(fold[rho * 4 + a], Elem<T>::ld(Dm + p * 16 + 4 * a + c), s);
+        Dp[i] = s;
+    }
+}
+
+// Gt[p][4 rho + c] = sum over the images' last tile rows of Yhat[p] * dC[rho][c] (rows rho >= nrho are zero) gives both
+//     dD[p][4a + c]  += sum_rho fold[rho][a] Gt[p][4 rho + c]        (added to the part from the complete tile rows)
+//     dfold[rho][a] (+)= sum_{p,c} Dm[p][4a + c] Gt[p][4 rho + c]    (fixed summation order)
+template <typename T>
+__global__ __launch_bounds__(256) void fold_grads_kernel(const float *__restrict__ Gt, const T *__restrict__ Dm,
+                                                         const float *__restrict__ fold, float *__restrict__ dD,
+                                                         float *__restrict__ dfold, int r, int nrho, int accumulate)
+{
+    if (dD)
+        for (int i = threadIdx.x; i < r * 16; i += 256) {
+            const int p = i >> 4, a = (i >> 2) & 3, c = i & 3;
+            float s = 0.f;
+            for (int rho = 0; rho < nrho; ++rho) s = fmaf(fold[rho * 4 + a], Gt[p * 16 + 4 * rho + c], s);
+            dD[i] += s;
+        }
+    if (dfold && threadIdx.x < nrho * 4) {
+        const int rho = threadIdx.x >> 2, a = threadIdx.x & 3;
+        float s = 0.f;
+        for (int p = 0; p < r; ++p)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) s = fmaf(Elem<T>::ld(Dm + p * 16 + 4 * a + c), Gt[p * 16 + 4 * rho + c], s);
+        dfold[threadIdx.x] = accumulate ? dfold[threadIdx.x] + s : s;
+    }
+}
+
+hipError_t launch_fold_decoder(int dtype, const void *Dm, const float *fold, float *Dp, int r, int nrho, hipStream_t s)
+{
+    if (dtype == 0) hipLaunchKernelGGL(fold_decoder_kernel<float>, dim3(1), dim3(256), 0, s, (const float *)Dm, fold, Dp, r, nrho);
+    else hipLaunchKernelGGL(fold_decoder_kernel<bf16_t>, dim3(1), dim3(256), 0, s, (const bf16_t *)Dm, fold, Dp, r, nrho);
+    return hipGetLastError();
+}
+
+hipError_t launch_fold_grads(int dtype, const float *Gt, const void *Dm, const float *fold, float *dD, float *dfold, int r,
+                             int nrho, int accumulate, hipStream_t s)
+{
+    if (dtype == 0)
+        hipLaunchKernelGGL(fold_grads_kernel<float>, dim3(1), dim3(256), 0, s, Gt, (const float *)Dm, fold, dD, dfold, r, nrho,
+                           accumulate);
+    else
+        hipLaunchKernelGGL(fold_grads_kernel<bf16_t>, dim3(1), dim3(256), 0, s, Gt, (const bf16_t *)Dm, fold, dD, dfold, r, nrho,
+                           accumulate);
+    return hipGetLastError();
 }
 
 // fp32 -> bf16 (round to nearest even), 8 elements per thread; n8 = number of 8-element groups, tail handled per element
@@ -485,44 +570,54 @@ hipError_t launch_cast_bf16(const float *in, void *out, size_t n, hipStream_t s)
     return hipGetLastError();
 }
 
-template <typename T>
-static hipError_t launch_encode_t(const void *A, const void *E, void *P, int R, int Cc, int r, int pg, hipStream_t s)
-{
-    dim3 block(64, 4), grid((Cc + 63) / 64, (R + 3) / 4);
-    hipLaunchKernelGGL(encode_kernel<T>, grid, block, 0, s, (const T *)A, (const T *)E, (T *)P, R, Cc, r, pg);
-    return hipGetLastError();
-}
-
-hipError_t launch_encode(int dtype, const void *A, const void *E, void *P, int R, int Cc, int r, int pg, hipStream_t s)
-{
-    if (pg <= 0) pg = R;
-    if (dtype == 1 && (Cc % 4) == 0) {
-        const int chunks = (Cc + 127) / 128;
-        const long items = (long)R * chunks;
-        hipLaunchKernelGGL(encode_mfma_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, (const bf16_t *)A,
-                           (const bf16_t *)E, (bf16_t *)P, R, Cc, r, chunks, pg);
-        return hipGetLastError();
-    }
-    return dtype == 0 ? launch_encode_t<float>(A, E, P, R, Cc, r, pg, s) : launch_encode_t<bf16_t>(A, E, P, R, Cc, r, pg, s);
-}
-
-template <typename T>
-static hipError_t launch_decode_t(const void *P, const void *Dm, void *Cmat, int R, int Cc, int r, bool gelu, int pg,
+template <typename T, typename TB>
+static hipError_t launch_encode_t(const void *A, const void *E, void *P, int Rs, int Cc, int r, int pg, const RowMap &rm,
                                   hipStream_t s)
 {
-    dim3 block(64, 4), grid((Cc + 63) / 64, (R + 3) / 4);
-    if (gelu)
-        hipLaunchKernelGGL((decode_kernel<T, true>), grid, block, 0, s, (const T *)P, (const T *)Dm, (T *)Cmat, R, Cc, r, pg);
-    else
-        hipLaunchKernelGGL((decode_kernel<T, false>), grid, block, 0, s, (const T *)P, (const T *)Dm, (T *)Cmat, R, Cc, r, pg);
+    dim3 block(64, 4), grid((Cc + 63) / 64, (Rs + 3) / 4);
+    hipLaunchKernelGGL((encode_kernel<T, TB>), grid, block, 0, s, (const T *)A, (const TB *)E, (T *)P, Rs, Cc, r, pg, rm);
     return hipGetLastError();
 }
 
-hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, int R, int Cc, int r, bool gelu, int pg,
-                         hipStream_t s)
+hipError_t launch_encode(int dtype, const void *A, const void *E, void *P, int R, int Cc, int r, int pg, hipStream_t s,
+                         RowMap rm, bool basis_f32)
 {
     if (pg <= 0) pg = R;
-    if (dtype == 1 && (Cc % 8) == 0) {
+    const int Rs = rm.count(R);                             // tile rows this launch walks over
+    if (Rs <= 0) return hipSuccess;
+    if (dtype == 1 && (Cc % 4) == 0 && !basis_f32) {
+        const int chunks = (Cc + 127) / 128;
+        const long items = (long)Rs * chunks;
+        hipLaunchKernelGGL(encode_mfma_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, (const bf16_t *)A,
+                           (const bf16_t *)E, (bf16_t *)P, Rs, Cc, r, chunks, pg, rm);
+        return hipGetLastError();
+    }
+    if (dtype == 0) return launch_encode_t<float, float>(A, E, P, Rs, Cc, r, pg, rm, s);
+    return basis_f32 ? launch_encode_t<bf16_t, float>(A, E, P, Rs, Cc, r, pg, rm, s)
+                     : launch_encode_t<bf16_t, bf16_t>(A, E, P, Rs, Cc, r, pg, rm, s);
+}
+
+template <typename T, typename TB>
+static hipError_t launch_decode_t(const void *P, const void *Dm, void *Cmat, int Rs, int Cc, int r, bool gelu, int pg,
+                                  const RowMap &rm, hipStream_t s)
+{
+    dim3 block(64, 4), grid((Cc + 63) / 64, (Rs + 3) / 4);
+    if (gelu)
+        hipLaunchKernelGGL((decode_kernel<T, TB, true>), grid, block, 0, s, (const T *)P, (const TB *)Dm, (T *)Cmat, Rs, Cc, r,
+                           pg, rm);
+    else
+        hipLaunchKernelGGL((decode_kernel<T, TB, false>), grid, block, 0, s, (const T *)P, (const TB *)Dm, (T *)Cmat, Rs, Cc, r,
+                           pg, rm);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, int R_all, int Cc, int r, bool gelu, int pg,
+                         hipStream_t s, RowMap rm, bool basis_f32)
+{
+    if (pg <= 0) pg = R_all;
+    const int R = rm.count(R_all);                          // tile rows this launch walks over
+    if (R <= 0) return hipSuccess;
+    if (dtype == 1 && (Cc % 8) == 0 && !basis_f32) {
         const int chunks = (Cc + 63) / 64;
         const long items = (long)R * chunks;
         long blocks = (items + 3) / 4;
@@ -531,16 +626,17 @@ hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, i
         const bf16_t *p = (const bf16_t *)P, *d = (const bf16_t *)Dm;
         bf16_t *c = (bf16_t *)Cmat;
         if (r <= 32) {
-            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 1, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr, pg);
-            else hipLaunchKernelGGL((decode_mfma_kernel<false, 1, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr, pg);
+            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 1, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr, pg, rm);
+            else hipLaunchKernelGGL((decode_mfma_kernel<false, 1, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr, pg, rm);
         } else {
-            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 2, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr, pg);
-            else hipLaunchKernelGGL((decode_mfma_kernel<false, 2, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr, pg);
+            if (gelu) hipLaunchKernelGGL((decode_mfma_kernel<true, 2, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr, pg, rm);
+            else hipLaunchKernelGGL((decode_mfma_kernel<false, 2, false>), grid, block, 0, s, p, d, c, R, Cc, r, chunks, nullptr, nullptr, pg, rm);
         }
         return hipGetLastError();
     }
-    return dtype == 0 ? launch_decode_t<float>(P, Dm, Cmat, R, Cc, r, gelu, pg, s)
-                      : launch_decode_t<bf16_t>(P, Dm, Cmat, R, Cc, r, gelu, pg, s);
+    if (dtype == 0) return launch_decode_t<float, float>(P, Dm, Cmat, R, Cc, r, gelu, pg, rm, s);
+    return basis_f32 ? launch_decode_t<bf16_t, float>(P, Dm, Cmat, R, Cc, r, gelu, pg, rm, s)
+                     : launch_decode_t<bf16_t, bf16_t>(P, Dm, Cmat, R, Cc, r, gelu, pg, rm, s);
 }
 
 hipError_t launch_outer_final(const float *part, float *G, int nb, int n_out, int accumulate, hipStream_t s)
@@ -558,18 +654,20 @@ int decode_outer_blocks(int R, int Cc)
     return (int)(blocks > 1024 ? 1024 : blocks);
 }
 
-hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const void *V, float *G, float *part, int R,
-                               int Cc, int r, int accumulate, int pg, hipStream_t s)
+hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const void *V, float *G, float *part, int R_all,
+                               int Cc, int r, int accumulate, int pg, hipStream_t s, RowMap rm)
 {
-    if (pg <= 0) pg = R;
+    if (pg <= 0) pg = R_all;
+    const int R = rm.count(R_all);
+    if (R <= 0) return hipErrorInvalidValue;
     const int chunks = (Cc + 63) / 64;
     const int nb = decode_outer_blocks(R, Cc);
     const bf16_t *p = (const bf16_t *)P, *d = (const bf16_t *)Dm, *v = (const bf16_t *)V;
     bf16_t *c = (bf16_t *)Cmat;
     if (r <= 32)
-        hipLaunchKernelGGL((decode_mfma_kernel<false, 1, true>), dim3(nb), dim3(256), 0, s, p, d, c, R, Cc, r, chunks, v, part, pg);
+        hipLaunchKernelGGL((decode_mfma_kernel<false, 1, true>), dim3(nb), dim3(256), 0, s, p, d, c, R, Cc, r, chunks, v, part, pg, rm);
     else
-        hipLaunchKernelGGL((decode_mfma_kernel<false, 2, true>), dim3(nb), dim3(256), 0, s, p, d, c, R, Cc, r, chunks, v, part, pg);
+        hipLaunchKernelGGL((decode_mfma_kernel<false, 2, true>), dim3(nb), dim3(256), 0, s, p, d, c, R, Cc, r, chunks, v, part, pg, rm);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int n_out = r * 16;
@@ -591,22 +689,24 @@ int outer_reduce_blocks(int64_t tiles)
     return (int)((tiles + tpb - 1) / tpb);
 }
 
-hipError_t launch_outer_reduce(int dtype, const void *P, const void *V, float *G, float *part, int R, int Cc, int r,
-                               int accumulate, int pg, hipStream_t s)
+hipError_t launch_outer_reduce(int dtype, const void *P, const void *V, float *G, float *part, int R_all, int Cc, int r,
+                               int accumulate, int pg, hipStream_t s, RowMap rm)
 {
-    if (pg <= 0) pg = R;
+    if (pg <= 0) pg = R_all;
+    const int R = rm.count(R_all);
+    if (R <= 0) return hipErrorInvalidValue;
     const int64_t tiles = (int64_t)R * Cc;
     const int tpb = outer_tiles_per_block(tiles);
     const int nb = outer_reduce_blocks(tiles);
     if (dtype == 0)
         hipLaunchKernelGGL(outer_partial_kernel<float>, dim3(nb), dim3(256), 0, s, (const float *)P, (const float *)V,
-                           part, R, Cc, r, tpb, pg);
+                           part, R, Cc, r, tpb, pg, rm);
     else if (Cc % 8 == 0)
         hipLaunchKernelGGL(outer_mfma_kernel, dim3(nb), dim3(256), 0, s, (const bf16_t *)P, (const bf16_t *)V, part, R,
-                           Cc, r, tpb, pg);
+                           Cc, r, tpb, pg, rm);
     else
         hipLaunchKernelGGL(outer_partial_kernel<bf16_t>, dim3(nb), dim3(256), 0, s, (const bf16_t *)P,
-                           (const bf16_t *)V, part, R, Cc, r, tpb, pg);
+                           (const bf16_t *)V, part, R, Cc, r, tpb, pg, rm);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int n_out = r * 16;

@@ -95,6 +95,26 @@ def aa_problem(nbatch, m, k, n, r, seed, dtype="bf16", t=4, with_dC=False):
     return out
 
 
+def ragged_problem(nimg, rows, k, n, r, seed, dtype="bf16", t=4, with_dC=False):
+    """Images of `rows` token rows each (197 in the ViT workload), stacked: X (nimg*rows, k) ~ N(0,1), encoded weight
+    planes ~ N(0, 1/k), bases ~ N(0, 1/16), fold coefficients (rows mod t, t) = "keep the real rows" plus N(0, 1/16) noise
+    (fp32 whatever the dtype), dC ~ N(0,1).  Draw order: X, What, E_X, D, fold, dC."""
+    if k % t or n % t:
+        raise ValueError("k, n must be divisible by t")
+    rng = np.random.default_rng(seed)
+    nrho = rows % t
+    out = {
+        "X": _normal(rng, (nimg * rows, k), 1.0, dtype),
+        "What": _normal(rng, (r, k // t, n // t), k ** -0.5, dtype),
+        "E_X": _normal(rng, (r, t * t), 0.25, dtype),
+        "D": _normal(rng, (r, t * t), 0.25, dtype),
+        "fold": (np.eye(nrho, t, dtype=np.float32) + _normal(rng, (nrho, t), 0.25, "f32")) if nrho else None,
+    }
+    if with_dC:
+        out["dC"] = _normal(rng, (nimg * rows, n), 1.0, dtype)
+    return out
+
+
 def config_problem(name, r=None, with_dC=False):
     """Inputs of a named workload (optionally with another r for the sweep)."""
     c = dict(CONFIGS[name])

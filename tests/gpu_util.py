@@ -190,3 +190,53 @@ def aa_backward(A, B, E_A, E_B, D, dC, nb, dtype, saved=None, accumulate=0, init
                         a["dD"], accumulate, ws, nbytes)
     torch.cuda.synchronize()
     return {k_: host(v) for k_, v in outs.items()}
+
+
+def _f32dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def ragged_forward(p, rows, dtype, save=False):
+    """p: dict with X (nimg*rows, k), What, E_X, D, fold.  Returns C (and Xhat, Yhat plane-major over the padded tile rows)."""
+    m, k = p["X"].shape
+    r, K, N = p["What"].shape
+    prob = stl.Problem(m, k, 4 * N, r, STL_DT[dtype])
+    X, What, E_X, D = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D"))
+    fold = _f32dev(p.get("fold"))
+    Rp = (m // rows) * ((rows + 3) // 4)
+    C = torch.full((m, 4 * N), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
+    Xh = planes_buffer(r, Rp, K, dtype) if save else None
+    Yh = planes_buffer(r, Rp, N, dtype) if save else None
+    nbytes = stl.stl_ragged_workspace_bytes(prob, rows, stl.STL_OP_FORWARD)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    stl.stl_ragged_forward(prob, rows, X, What, E_X, D, fold, C, Xh, Yh, ws, nbytes)
+    torch.cuda.synchronize()
+    if save:
+        return host(C), planes_to_host(Xh, r, Rp, K), planes_to_host(Yh, r, Rp, N)
+    return host(C)
+
+
+def ragged_backward(p, rows, dtype, saved=None, accumulate=0, init=None, skip=()):
+    """Returns dict(dX, dWhat, dE_X, dD, dfold) as float64 numpy.  saved: (Xhat, Yhat) plane-major numpy or None."""
+    m, k = p["X"].shape
+    r, K, N = p["What"].shape
+    nrho = rows % 4
+    prob = stl.Problem(m, k, 4 * N, r, STL_DT[dtype])
+    X, What, E_X, D, dC = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D", "dC"))
+    fold = _f32dev(p.get("fold"))
+    sv = [planes_to_dev(x, dtype) for x in saved] if saved is not None else [None, None]
+    nan = float("nan")
+    f32 = dict(dtype=torch.float32, device="cuda")
+    outs = {"dX": torch.full((m, k), nan, dtype=TORCH_DT[dtype], device="cuda")}
+    shapes = {"dWhat": (r, K, N), "dE_X": (r, 16), "dD": (r, 16), "dfold": (max(nrho, 1), 4)}
+    for i, (name, shp) in enumerate(shapes.items()):
+        outs[name] = torch.full(shp, nan, **f32) if init is None else _f32dev(init[i])
+    a = {k_: (None if k_ in skip else v) for k_, v in outs.items()}
+    nbytes = stl.stl_ragged_workspace_bytes(prob, rows, stl.STL_OP_BACKWARD)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    stl.stl_ragged_backward(prob, rows, X, What, E_X, D, fold, dC, sv[0], sv[1], a["dX"], a["dWhat"], a["dE_X"], a["dD"],
+                            a["dfold"], accumulate, ws, nbytes)
+    torch.cuda.synchronize()
+    res = {k_: host(v) for k_, v in outs.items()}
+    res["dfold"] = res["dfold"][:nrho] if nrho else None
+    return res

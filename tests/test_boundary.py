@@ -178,3 +178,61 @@ def test_plane_layout_helpers():
     for (p, I, J) in [(0, 0, 0), (2, 63, 7), (1, 64, 0), (2, 99, 3)]:
         assert flat[((I // 64) * r + p) * 64 * Cc + (I % 64) * Cc + J] == a[p, I, J]
     assert np.array_equal(gpu_util.ungroup_planes(flat, r, R, Cc), a)
+
+
+def test_two_activation_argument_checks():
+    prob = stl.Problem(256, 64, 256, 32, stl.STL_BF16)
+    F, B = stl.STL_OP_FORWARD, stl.STL_OP_BACKWARD
+    fwd, bwd = stl.stl_aa_workspace_bytes(prob, 4, F), stl.stl_aa_workspace_bytes(prob, 4, B)
+    # stacked planes of A, B and Yhat; the backward adds their three gradients
+    planes_bytes = 2 * (stl.stl_plane_elems(4 * 64, 16, 32) + stl.stl_plane_elems(4 * 16, 64, 32) + stl.stl_plane_elems(4 * 64, 64, 32))
+    assert fwd == planes_bytes and bwd > 2 * planes_bytes
+    assert stl.stl_aa_workspace_bytes(prob, 8, F) > fwd
+    assert stl.stl_aa_workspace_bytes(prob, 0, F) == 0 and stl.stl_aa_workspace_bytes(prob, 4, 7) == 0
+    assert stl.stl_aa_workspace_bytes(prob, 1 << 20, F) == 0          # stacked rows beyond the cap
+    ok = [FAKE] * 6 + [None] * 3
+    for nb, args, ws, flags, status in ((0, ok, (FAKE, 1 << 40), 0, 1), (4, [None] + ok[1:], (FAKE, 1 << 40), 0, 1),
+                                        (4, ok, (FAKE, fwd - 1), 0, 3), (4, ok, (None, 0), 0, 3),
+                                        (4, ok, (FAKE, 1 << 40), 0x200, 2), (4, ok, (FAKE, 1 << 40), stl.STL_FLAG_FUSED, 2),
+                                        (4, [FAKE + 4] + ok[1:], (FAKE, 1 << 40), 0, 1)):
+        with pytest.raises(stl.StlError) as e:
+            stl.stl_aa_forward(prob, nb, *args, *ws, flags, stream=0)
+        assert e.value.status == status, (nb, args, ws, flags)
+    okb = [FAKE] * 6 + [None] * 3 + [FAKE] * 5
+    for nb, args, acc, ws, status in ((4, okb[:5] + [None] + okb[6:], 0, (FAKE, 1 << 40), 1), (4, okb, 2, (FAKE, 1 << 40), 1),
+                                      (4, okb, 0, (FAKE, bwd - 1), 3), (-1, okb, 0, (FAKE, 1 << 40), 1)):
+        with pytest.raises(stl.StlError) as e:
+            stl.stl_aa_backward(prob, nb, *args, acc, *ws, stream=0)
+        assert e.value.status == status
+
+
+def test_ragged_argument_checks():
+    """Images of 197 rows: m must be a multiple of the rows per image, the fold is required when rows % 4 != 0."""
+    prob = stl.Problem(8 * 197, 256, 512, 32, stl.STL_BF16)
+    F, B = stl.STL_OP_FORWARD, stl.STL_OP_BACKWARD
+    fwd, bwd = stl.stl_ragged_workspace_bytes(prob, 197, F), stl.stl_ragged_workspace_bytes(prob, 197, B)
+    planes_bytes = 2 * (stl.stl_plane_elems(8 * 50, 64, 32) + stl.stl_plane_elems(8 * 50, 128, 32))   # over the padded tile rows
+    assert planes_bytes < fwd < planes_bytes + 8192 and bwd > 2 * planes_bytes
+    assert stl.stl_ragged_workspace_bytes(prob, 196, F) == 0          # 8*197 is not a multiple of 196
+    assert stl.stl_ragged_workspace_bytes(prob, 3, F) == 0
+    assert stl.stl_ragged_workspace_bytes(prob, 197, 9) == 0
+    ok = [FAKE] * 6 + [None, None]
+    for rows, args, ws, status in ((196, ok, (FAKE, 1 << 40), 1), (3, ok, (FAKE, 1 << 40), 1),
+                                   (197, ok[:4] + [None] + ok[5:], (FAKE, 1 << 40), 1),      # fold missing
+                                   (197, ok[:5] + [None] + ok[6:], (FAKE, 1 << 40), 1),      # C missing
+                                   (197, ok, (FAKE, fwd - 1), 3), (197, ok, (None, 0), 3),
+                                   (197, ok[:4] + [FAKE + 4] + ok[5:], (FAKE, 1 << 40), 1)):
+        with pytest.raises(stl.StlError) as e:
+            stl.stl_ragged_forward(prob, rows, *args, *ws, stream=0)
+        assert e.value.status == status, (rows, args, ws)
+    okb = [FAKE] * 6 + [None, None] + [FAKE] * 5
+    for rows, args, acc, ws, status in ((197, okb, 3, (FAKE, 1 << 40), 1), (197, okb, 0, (FAKE, bwd - 1), 3),
+                                        (197, okb[:5] + [None] + okb[6:], 0, (FAKE, 1 << 40), 1), (200, okb, 0, (FAKE, 1 << 40), 1)):
+        with pytest.raises(stl.StlError) as e:
+            stl.stl_ragged_backward(prob, rows, *args, acc, *ws, stream=0)
+        assert e.value.status == status
+    # a divisible row count needs no fold: the same call passes validation up to the workspace check
+    even = stl.Problem(8 * 196, 256, 512, 32, stl.STL_BF16)
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_ragged_forward(even, 196, FAKE, FAKE, FAKE, FAKE, None, FAKE, None, None, None, 0, stream=0)
+    assert e.value.status == 3

@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--sweep-big", action="store_true", help="with --sweep: include n=16384 in the square sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mlp", action="store_true", help="skip the stacked-layer (MLP-shaped pair) leg")
+    ap.add_argument("--extra", action="store_true",
+                    help="also time the forward passes of the two-activation and ragged-row entry points")
     ap.add_argument("--profile-only", default="",
                     help="run only this leg (forward|backward|step|stages|copy|mlp) a few times")
     return ap.parse_args()
@@ -204,6 +206,37 @@ def main():
         calls["dense"] = dense_pair
         return (mm, d_, h_, rr), calls
 
+    # Forward passes of the two later entry points at the full-size shapes their GPU parity tests run
+    # (tests/test_gpu_aa.py, tests/test_gpu_ragged.py), against the dense products on the same rows.
+    def aa_setup():
+        nbt, ma, ka, na = 32, 1024, 128, 1024              # attention scores: 32 (head, image) pairs, 1024 tokens, head width 128
+        q = stl_synth.aa_problem(nbt, ma, ka, na, 32, 8400, "bf16")
+        A_, B_, Ea, Eb, Dd = (dev(q[s]) for s in ("A", "B", "E_A", "E_B", "D"))
+        pa = stl.Problem(ma, ka, na, 32, stl.STL_BF16)
+        Ca = torch.empty((nbt * ma, na), dtype=bf, device="cuda")
+        nfa = stl.stl_aa_workspace_bytes(pa, nbt, stl.STL_OP_FORWARD)
+        wfa = torch.empty(nfa, dtype=torch.uint8, device="cuda")
+        A3, B3, C3 = A_.view(nbt, ma, ka), B_.view(nbt, ka, na), Ca.view(nbt, ma, na)
+        calls = {"stl_forward": lambda: stl.stl_aa_forward(pa, nbt, A_, B_, Ea, Eb, Dd, Ca, None, None, None, wfa, nfa, 0),
+                 "dense_forward": lambda: torch.bmm(A3, B3, out=C3)}
+        return (f"attention scores, {nbt} x ({ma} x {ka} x {na}), both operands encoded at run time, r=32, bf16, forward; "
+                "dense = torch.bmm"), calls
+
+    def ragged_setup():
+        nimg, rows_, kr, nr = 256, 197, 768, 3072          # 256 images of 197 tokens, 768 -> 3072
+        q = stl_synth.ragged_problem(nimg, rows_, kr, nr, 32, 9400, "bf16")
+        Xr, Wr, Er, Dr = (dev(q[s]) for s in ("X", "What", "E_X", "D"))
+        fold = torch.from_numpy(q["fold"]).cuda()
+        pr_ = stl.Problem(nimg * rows_, kr, nr, 32, stl.STL_BF16)
+        Cr = torch.empty((nimg * rows_, nr), dtype=bf, device="cuda")
+        nfr = stl.stl_ragged_workspace_bytes(pr_, rows_, stl.STL_OP_FORWARD)
+        wfr = torch.empty(nfr, dtype=torch.uint8, device="cuda")
+        Wdr = (torch.randn((kr, nr), device="cuda") * kr ** -0.5).to(bf)
+        calls = {"stl_forward": lambda: stl.stl_ragged_forward(pr_, rows_, Xr, Wr, Er, Dr, fold, Cr, None, None, wfr, nfr),
+                 "dense_forward": lambda: torch.matmul(Xr, Wdr, out=Cr)}
+        return (f"{nimg} images x {rows_} tokens, {kr} -> {nr}, r=32, bf16, forward with the fold of the last tile row; "
+                "dense = matmul on the same rows"), calls
+
     if args.profile_only:
         cal_src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda")
         cal_dst = torch.empty_like(cal_src)
@@ -214,6 +247,10 @@ def main():
                                    stl.stl_decode(prob, Yhat, D, C))}
         if args.profile_only == "mlp":
             legs["mlp"] = mlp_setup()[1]["one_pass"]
+        if args.profile_only == "aa":
+            legs["aa"] = aa_setup()[1]["stl_forward"]
+        if args.profile_only == "ragged":
+            legs["ragged"] = ragged_setup()[1]["stl_forward"]
         fwd()
         T.ramp(legs[args.profile_only])                 # clocks up first, as in the timed run (these calls are traced too)
         for _ in range(max(args.steps, 1)):
@@ -337,6 +374,18 @@ def main():
                            "speedup_vs_dense": round(pair["dense"] / pair["one_pass"], 4)}
         log(f"  stacked layers (ms): {pair}")
         del calls
+
+    if args.extra:
+        aa_w, aa_calls = aa_setup()
+        aa = {name: round(T.wall(fn, max(S // 2, 2), max(W // 2, 1)), 5) for name, fn in aa_calls.items()}
+        out["two_activations"] = {"workload": aa_w, "ms": aa}
+        log(f"  two activations (ms): {aa}")
+        del aa_calls
+        rg_w, rg_calls = ragged_setup()
+        rag = {name: round(T.wall(fn, max(S // 2, 2), max(W // 2, 1)), 5) for name, fn in rg_calls.items()}
+        out["ragged_rows"] = {"workload": rg_w, "ms": rag}
+        log(f"  ragged rows (ms): {rag}")
+        del rg_calls
 
     if args.sweep:
         sweep = {}

@@ -477,10 +477,9 @@ bool plane_gemm_pipe_eligible(const GemmDesc &g)
     if (g.a_kmajor && g.a_rows_per_group() % pipe::BKS) return false;
     if (g.b_kmajor && g.b_rows_per_group() % pipe::BKS) return false;
     if (g.o_pg > 0 && g.o_pg % 32) return false;
-    // stacked problems: every problem's first stored row keeps those alignments
-    if (g.nb > 1 && ((g.a_kmajor && g.a_pg > 0 && g.Kl % pipe::BKS) || (g.b_kmajor && g.b_pg > 0 && g.Kl % pipe::BKS) ||
-                     (g.o_pg > 0 && g.Mi % 32)))
-        return false;
+    // stacked problems: every problem's first stored row keeps those alignments; only the single-stage contraction
+    // (attention-shaped products) is taken here, deeper stacked contractions go to the register-staged kernel
+    if (g.nb > 1 && (g.Kl != pipe::BKS || (g.o_pg > 0 && g.Mi % 32))) return false;
     // a clamped edge chunk must still lie inside the operand
     if (g.Mi < 8 || g.Nj < 8) return false;
     return g.Mi > 128 && g.Nj > 128;

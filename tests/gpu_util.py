@@ -57,6 +57,31 @@ def planes_to_host(t, r, R, Cc):
     return ungroup_planes(host(t), r, R, Cc)
 
 
+class Guard:
+    """Device buffers with 4 KB of sentinel bytes on either side: check() fails if a kernel wrote outside a buffer it
+    was given (reads outside cannot be seen this way)."""
+    PAD, BYTE = 4096, 0xA5
+
+    def __init__(self):
+        self.bufs = []
+
+    def alloc(self, shape, dtype, fill=float("nan")):
+        n = int(np.prod(shape))
+        es = torch.empty((), dtype=dtype).element_size()
+        raw = torch.full((n * es + 2 * self.PAD,), self.BYTE, dtype=torch.uint8, device="cuda")
+        body = raw[self.PAD:self.PAD + n * es].view(dtype).view(*shape)
+        if fill is not None:
+            body.fill_(fill)
+        self.bufs.append(raw)
+        return body
+
+    def check(self):
+        torch.cuda.synchronize()
+        for i, raw in enumerate(self.bufs):
+            lo, hi = raw[:self.PAD], raw[-self.PAD:]
+            assert bool((lo == self.BYTE).all()) and bool((hi == self.BYTE).all()), f"buffer {i}: write outside its bounds"
+
+
 def workspace(prob, op, flags=0):
     nbytes = stl.stl_workspace_bytes(prob, op, flags)
     return torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda"), nbytes
@@ -159,13 +184,14 @@ def aa_forward(A, B, E_A, E_B, D, nb, dtype, flags=0, save=False):
     m, k, n, r = A.shape[0] // nb, A.shape[1], B.shape[1], D.shape[0]
     prob = stl.Problem(m, k, n, r, STL_DT[dtype])
     Ad, Bd, Ea, Eb, Dd = (dev(x, dtype) for x in (A, B, E_A, E_B, D))
-    C = torch.full((nb * m, n), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
+    gd = Guard()
+    C = gd.alloc((nb * m, n), TORCH_DT[dtype])
     shapes = [(nb * m // 4, k // 4), (nb * k // 4, n // 4), (nb * m // 4, n // 4)]
-    bufs = [planes_buffer(r, R, Cc, dtype) for R, Cc in shapes] if save else [None] * 3
+    bufs = [gd.alloc((stl.stl_plane_elems(R, Cc, r),), TORCH_DT[dtype]) for R, Cc in shapes] if save else [None] * 3
     nbytes = stl.stl_aa_workspace_bytes(prob, nb, stl.STL_OP_FORWARD)
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    ws = gd.alloc((max(nbytes, 16),), torch.uint8, fill=None)
     stl.stl_aa_forward(prob, nb, Ad, Bd, Ea, Eb, Dd, C, bufs[0], bufs[1], bufs[2], ws, nbytes, flags)
-    torch.cuda.synchronize()
+    gd.check()
     if save:
         return (host(C),) + tuple(planes_to_host(b, r, R, Cc) for b, (R, Cc) in zip(bufs, shapes))
     return host(C)
@@ -177,18 +203,18 @@ def aa_backward(A, B, E_A, E_B, D, dC, nb, dtype, saved=None, accumulate=0, init
     prob = stl.Problem(m, k, n, r, STL_DT[dtype])
     Ad, Bd, Ea, Eb, Dd, dCd = (dev(x, dtype) for x in (A, B, E_A, E_B, D, dC))
     sv = [planes_to_dev(x, dtype) for x in saved] if saved is not None else [None] * 3
-    nan = float("nan")
-    outs = {"dA": torch.full((nb * m, k), nan, dtype=TORCH_DT[dtype], device="cuda"),
-            "dB": torch.full((nb * k, n), nan, dtype=TORCH_DT[dtype], device="cuda")}
+    gd = Guard()
+    outs = {"dA": gd.alloc((nb * m, k), TORCH_DT[dtype]), "dB": gd.alloc((nb * k, n), TORCH_DT[dtype])}
     for i, name in enumerate(("dE_A", "dE_B", "dD")):
-        outs[name] = (torch.full((r, 16), nan, dtype=torch.float32, device="cuda") if init is None
-                      else torch.from_numpy(np.asarray(init[i], dtype=np.float32)).cuda())
+        outs[name] = gd.alloc((r, 16), torch.float32)
+        if init is not None:
+            outs[name].copy_(torch.from_numpy(np.asarray(init[i], dtype=np.float32)))
     a = {k_: (None if k_ in skip else v) for k_, v in outs.items()}
     nbytes = stl.stl_aa_workspace_bytes(prob, nb, stl.STL_OP_BACKWARD)
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    ws = gd.alloc((max(nbytes, 16),), torch.uint8, fill=None)
     stl.stl_aa_backward(prob, nb, Ad, Bd, Ea, Eb, Dd, dCd, sv[0], sv[1], sv[2], a["dA"], a["dB"], a["dE_A"], a["dE_B"],
                         a["dD"], accumulate, ws, nbytes)
-    torch.cuda.synchronize()
+    gd.check()
     return {k_: host(v) for k_, v in outs.items()}
 
 
@@ -204,13 +230,14 @@ def ragged_forward(p, rows, dtype, save=False):
     X, What, E_X, D = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D"))
     fold = _f32dev(p.get("fold"))
     Rp = (m // rows) * ((rows + 3) // 4)
-    C = torch.full((m, 4 * N), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
-    Xh = planes_buffer(r, Rp, K, dtype) if save else None
-    Yh = planes_buffer(r, Rp, N, dtype) if save else None
+    gd = Guard()
+    C = gd.alloc((m, 4 * N), TORCH_DT[dtype])
+    Xh = gd.alloc((stl.stl_plane_elems(Rp, K, r),), TORCH_DT[dtype]) if save else None
+    Yh = gd.alloc((stl.stl_plane_elems(Rp, N, r),), TORCH_DT[dtype]) if save else None
     nbytes = stl.stl_ragged_workspace_bytes(prob, rows, stl.STL_OP_FORWARD)
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    ws = gd.alloc((max(nbytes, 16),), torch.uint8, fill=None)
     stl.stl_ragged_forward(prob, rows, X, What, E_X, D, fold, C, Xh, Yh, ws, nbytes)
-    torch.cuda.synchronize()
+    gd.check()
     if save:
         return host(C), planes_to_host(Xh, r, Rp, K), planes_to_host(Yh, r, Rp, N)
     return host(C)
@@ -225,18 +252,19 @@ def ragged_backward(p, rows, dtype, saved=None, accumulate=0, init=None, skip=()
     X, What, E_X, D, dC = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D", "dC"))
     fold = _f32dev(p.get("fold"))
     sv = [planes_to_dev(x, dtype) for x in saved] if saved is not None else [None, None]
-    nan = float("nan")
-    f32 = dict(dtype=torch.float32, device="cuda")
-    outs = {"dX": torch.full((m, k), nan, dtype=TORCH_DT[dtype], device="cuda")}
+    gd = Guard()
+    outs = {"dX": gd.alloc((m, k), TORCH_DT[dtype])}
     shapes = {"dWhat": (r, K, N), "dE_X": (r, 16), "dD": (r, 16), "dfold": (max(nrho, 1), 4)}
     for i, (name, shp) in enumerate(shapes.items()):
-        outs[name] = torch.full(shp, nan, **f32) if init is None else _f32dev(init[i])
+        outs[name] = gd.alloc(shp, torch.float32)
+        if init is not None:
+            outs[name].copy_(_f32dev(init[i]))
     a = {k_: (None if k_ in skip else v) for k_, v in outs.items()}
     nbytes = stl.stl_ragged_workspace_bytes(prob, rows, stl.STL_OP_BACKWARD)
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+    ws = gd.alloc((max(nbytes, 16),), torch.uint8, fill=None)
     stl.stl_ragged_backward(prob, rows, X, What, E_X, D, fold, dC, sv[0], sv[1], a["dX"], a["dWhat"], a["dE_X"], a["dD"],
                             a["dfold"], accumulate, ws, nbytes)
-    torch.cuda.synchronize()
+    gd.check()
     res = {k_: host(v) for k_, v in outs.items()}
     res["dfold"] = res["dfold"][:nrho] if nrho else None
     return res

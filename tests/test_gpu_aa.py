@@ -20,13 +20,14 @@ def _ref_forward(p, nb):
 
 CASES = [
     # dtype, nbatch, m, k, n, r
-    ("bf16", 3, 256, 128, 256, 32),     # pipelined plane products on stacked problems (all alignments hold)
-    ("bf16", 2, 512, 256, 384, 24),     # a ragged last 256-column block
-    ("bf16", 4, 200, 64, 200, 32),      # attention-shaped: 200 tokens, head width 64 (second matrix-core path)
+    ("bf16", 3, 256, 128, 256, 32),     # register-staged matrix-core plane products on stacked problems
+    ("bf16", 2, 512, 256, 384, 24),
+    ("bf16", 4, 200, 64, 200, 32),      # attention-shaped: 200 tokens, head width 64 (50 tile rows: any-shape plane products)
     ("bf16", 3, 200, 200, 64, 16),      # attention x values
     ("bf16", 5, 72, 40, 56, 49),        # nothing a multiple of 32; two 32-plane groups
     ("bf16", 2, 36, 20, 28, 7),         # tile counts not multiples of 8: generic kernels
     ("bf16", 1, 128, 128, 128, 32),     # nbatch = 1
+    ("bf16", 2, 1024, 640, 768, 16),    # stacked problems on the 256 x 256 tiles of the register-staged kernel
     ("f32", 3, 64, 32, 48, 17),
     ("f32", 2, 8, 4, 4, 1),
 ]

@@ -53,3 +53,41 @@ def test_fp32_bilinearity_and_rank_additivity(gu):
         s = {"X": p["X"], "What": p["What"][sl], "E_X": p["E_X"][sl], "D": p["D"][sl]}
         part = part + gu.forward(s, "f32")
     assert gu.rel(part, gu.forward(p, "f32")) <= 1e-5
+
+
+small = st.integers(min_value=1, max_value=12).map(lambda v: 4 * v)
+
+
+@settings(max_examples=25, deadline=None, derandomize=True, database=None,
+          suppress_health_check=[HealthCheck.function_scoped_fixture])
+@given(nb=st.integers(1, 5), m=small, k=small, n=small, r=st.integers(1, 64), seed=st.integers(0, 2 ** 16),
+       dtype=st.sampled_from(["f32", "bf16"]))
+def test_two_activations_random_shapes(gu, nb, m, k, n, r, seed, dtype):
+    from oracle import planes
+    p = stl_synth.aa_problem(nb, m, k, n, r, seed=seed, dtype=dtype, with_dC=True)
+    args = (p["A"], p["B"], p["E_A"], p["E_B"], p["D"])
+    tol = gu.TOL[dtype]
+    assert gu.rel(gu.aa_forward(*args, nb, dtype), planes.aa_forward(*args, nbatch=nb)) <= tol
+    got = gu.aa_backward(*args, p["dC"], nb, dtype)
+    ref = planes.aa_backward(*args, p["dC"], nbatch=nb)
+    for name, g in zip(("dA", "dB", "dE_A", "dE_B", "dD"), ref):
+        assert gu.rel(got[name], g) <= tol, name
+
+
+@settings(max_examples=25, deadline=None, derandomize=True, database=None,
+          suppress_health_check=[HealthCheck.function_scoped_fixture])
+@given(nimg=st.integers(1, 5), rows=st.integers(4, 45), k=small, n=small, r=st.integers(1, 64), seed=st.integers(0, 2 ** 16),
+       dtype=st.sampled_from(["f32", "bf16"]))
+def test_ragged_rows_random_shapes(gu, nimg, rows, k, n, r, seed, dtype):
+    from oracle import planes
+    p = stl_synth.ragged_problem(nimg, rows, k, n, r, seed=seed, dtype=dtype, with_dC=True)
+    tol = gu.TOL[dtype]
+    ref = planes.ragged_forward(p["X"], p["What"], p["E_X"], p["D"], p["fold"], rows)
+    assert gu.rel(gu.ragged_forward(p, rows, dtype), ref) <= tol
+    got = gu.ragged_backward(p, rows, dtype)
+    refs = planes.ragged_backward(p["X"], p["What"], p["E_X"], p["D"], p["fold"], p["dC"], rows)
+    for name, g in zip(("dX", "dWhat", "dE_X", "dD", "dfold"), refs):
+        if g is None:
+            assert got[name] is None
+        else:
+            assert gu.rel(got[name], g) <= tol, name

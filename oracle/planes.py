@@ -117,41 +117,46 @@ def mlp_pair(X, What1, E_X1, D1, What2, E_X2, D2, t: int = 4, activation: str | 
 
 
 # ------------------------------------------------------------------ both operands encoded at run time
-def aa_forward(A, B, E_A, E_B, D, nbatch: int = 1, t: int = 4):
+def aa_forward(A, B, E_A, E_B, D, nbatch: int = 1, t: int = 4, b_transposed: bool = False):
     """STL of two activations (the attention products of the Class-1 discussion, where neither operand is a
     weight): the second operand is encoded at run time with E_B exactly as a weight is with E_W,
         Bhat[p, L, J] = sum_q E_B[p, q] b[L, J, q],   C = decode_D( encode_{E_A}(A)[p] @ Bhat[p] ).
     `nbatch` independent products (heads x images) are stacked along the rows: A is (nbatch*m, k), B is
-    (nbatch*k, n), C is (nbatch*m, n); the bases are shared by the whole batch."""
+    (nbatch*k, n), C is (nbatch*m, n); the bases are shared by the whole batch.
+    b_transposed: B holds the transposes, (nbatch*n, k) -- the Q K^T case with K stored tokens x width; the
+    operator is applied to B_b^T."""
     A = np.asarray(A, dtype=np.float64)
     B = np.asarray(B, dtype=np.float64)
-    m, k = A.shape[0] // nbatch, B.shape[0] // nbatch
-    if A.shape[0] != nbatch * m or B.shape[0] != nbatch * k or A.shape[1] != k:
+    m, rb = A.shape[0] // nbatch, B.shape[0] // nbatch
+    k = A.shape[1]
+    if A.shape[0] != nbatch * m or B.shape[0] != nbatch * rb or (B.shape[1] if b_transposed else rb) != k:
         raise ValueError("stacked operands do not match nbatch")
     out = []
     for b in range(nbatch):
-        Bhat = encode(B[b * k:(b + 1) * k], E_B, t)
+        Bb = B[b * rb:(b + 1) * rb]
+        Bhat = encode(Bb.T if b_transposed else Bb, E_B, t)
         out.append(forward(A[b * m:(b + 1) * m], Bhat, E_A, D, t))
     return np.concatenate(out, axis=0)
 
 
-def aa_backward(A, B, E_A, E_B, D, dC, nbatch: int = 1, t: int = 4):
+def aa_backward(A, B, E_A, E_B, D, dC, nbatch: int = 1, t: int = 4, b_transposed: bool = False):
     """Gradients of sum_b <dC_b, C_b> for :func:`aa_forward`: (dA, dB, dE_A, dE_B, dD).  Chain rule through the
     three steps for A (as for an activation) and through the run-time encoding for B (as for a weight); the
-    shared bases collect the sum over the batch."""
+    shared bases collect the sum over the batch.  dB has the shape B was given in."""
     A = np.asarray(A, dtype=np.float64)
     B = np.asarray(B, dtype=np.float64)
     dC = np.asarray(dC, dtype=np.float64)
-    m, k = A.shape[0] // nbatch, B.shape[0] // nbatch
+    m, rb = A.shape[0] // nbatch, B.shape[0] // nbatch
     dA, dB = np.zeros_like(A), np.zeros_like(B)
     dE_A, dE_B, dD = (np.zeros((np.asarray(D).shape[0], t * t)) for _ in range(3))
     for b in range(nbatch):
-        Ab, Bb = A[b * m:(b + 1) * m], B[b * k:(b + 1) * k]
+        Ab, Bs = A[b * m:(b + 1) * m], B[b * rb:(b + 1) * rb]
+        Bb = Bs.T if b_transposed else Bs
         Bhat = encode(Bb, E_B, t)
         dAb, dBhat, dEa, dDb = backward(Ab, Bhat, E_A, D, dC[b * m:(b + 1) * m], t)
         dBb, dEb = encode_weight_backward(Bb, E_B, dBhat, t)
         dA[b * m:(b + 1) * m] = dAb
-        dB[b * k:(b + 1) * k] = dBb
+        dB[b * rb:(b + 1) * rb] = dBb.T if b_transposed else dBb
         dE_A += dEa
         dE_B += dEb
         dD += dDb

@@ -404,6 +404,50 @@ def test_aa_backward_finite_differences_and_textbook():
         assert rel(dB[b * k:(b + 1) * k], Ab.T @ dCb) < 1e-12
 
 
+def test_aa_transposed_second_operand():
+    """Q K^T with K stored tokens x width: at the exact basis C_b = A_b @ B_b^T, dA_b = dC_b B_b, dB_b = dC_b^T A_b;
+    for a generic basis, tile by tile with the transposed tile written out (tile (L, J) of B^T is the transpose of
+    tile (J, L) of B), and finite differences on B in its stored shape."""
+    nb, m, k, n, r = 2, 8, 12, 4, 7
+    A = RNG.standard_normal((nb * m, k))
+    B = RNG.standard_normal((nb * n, k))              # stored transposed
+    dC = RNG.standard_normal((nb * m, n))
+    E_A, E_B, D = bases.strassen_4x4()
+    C = planes.aa_forward(A, B, E_A, E_B, D, nbatch=nb, b_transposed=True)
+    dA, dB, _, _, _ = planes.aa_backward(A, B, E_A, E_B, D, dC, nbatch=nb, b_transposed=True)
+    for b in range(nb):
+        Ab, Bb, dCb = A[b * m:(b + 1) * m], B[b * n:(b + 1) * n], dC[b * m:(b + 1) * m]
+        assert rel(C[b * m:(b + 1) * m], Ab @ Bb.T) < 1e-12
+        assert rel(dA[b * m:(b + 1) * m], dCb @ Bb) < 1e-12
+        assert rel(dB[b * n:(b + 1) * n], dCb.T @ Ab) < 1e-12
+    E_A, E_B, D = (RNG.standard_normal((r, 16)) * 0.5 for _ in range(3))
+    got = planes.aa_forward(A, B, E_A, E_B, D, nbatch=nb, b_transposed=True)
+    want = np.zeros((nb * m, n))
+    for b in range(nb):
+        for I in range(m // 4):
+            for J in range(n // 4):
+                acc = np.zeros(r)
+                for L in range(k // 4):
+                    a = A[b * m + 4 * I:b * m + 4 * I + 4, 4 * L:4 * L + 4].reshape(16)
+                    bt = B[b * n + 4 * J:b * n + 4 * J + 4, 4 * L:4 * L + 4].T.reshape(16)
+                    acc += (E_A @ a) * (E_B @ bt)
+                want[b * m + 4 * I:b * m + 4 * I + 4, 4 * J:4 * J + 4] = (D.T @ acc).reshape(4, 4)
+    assert rel(got, want) < 1e-13
+    loss = lambda B_: float(np.sum(dC * planes.aa_forward(A, B_, E_A, E_B, D, nbatch=nb, b_transposed=True)))
+    g = planes.aa_backward(A, B, E_A, E_B, D, dC, nbatch=nb, b_transposed=True)
+    assert g[1].shape == B.shape
+    base = loss(B)
+    for idx in [(0, 0), (3, 11), (7, 5)]:
+        Bp = B.copy()
+        Bp[idx] += 0.5
+        assert abs((loss(Bp) - base) / 0.5 - g[1][idx]) < 1e-9 * max(1.0, abs(g[1][idx]))
+    lossE = lambda E_: float(np.sum(dC * planes.aa_forward(A, B, E_A, E_, D, nbatch=nb, b_transposed=True)))
+    for idx in [(0, 1), (6, 14)]:
+        Ep = E_B.copy()
+        Ep[idx] += 0.5
+        assert abs((lossE(Ep) - base) / 0.5 - g[3][idx]) < 1e-9 * max(1.0, abs(g[3][idx]))
+
+
 # --------------------------------------------------------------- row counts that t does not divide
 def test_pad_and_fold_rows():
     """197-token images (Class-1 appendix): 3 null rows are appended per image; on the way back complete tile rows

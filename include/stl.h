@@ -82,7 +82,8 @@ enum {
     STL_FLAG_EPILOGUE = 2,  /* encode launch, then plane products with D applied in the epilogue   */
     STL_FLAG_FUSED = 3,     /* one launch: encode -> MFMA -> decode, no plane ever written to HBM   */
     STL_FLAG_VARIANT_MASK = 0xff,
-    STL_FLAG_GELU = 0x100   /* C <- gelu(C) (exact erf form) applied in fp32 before the final rounding */
+    STL_FLAG_GELU = 0x100,  /* C <- gelu(C) (exact erf form) applied in fp32 before the final rounding */
+    STL_FLAG_B_TRANSPOSED = 0x200   /* stl_aa_*: the second operand is stored transposed, (nbatch*n) x k */
 };
 
 /* Bytes of device scratch `ws` needed by op (STL_OP_*) with `flags`; 0 on invalid problem. */
@@ -194,7 +195,11 @@ stl_status_t stl_recode(const stl_problem_t *up, const stl_problem_t *down, cons
  * All plane tensors are activation-side (grouped layout) over the stacked tile rows:
  *   Ahat stl_plane_elems(nbatch*M, K, r), Bhat stl_plane_elems(nbatch*K, N, r), Yhat stl_plane_elems(nbatch*M, N, r)
  * elements.  *_save: NULL or a buffer that receives the tensor for stl_aa_backward.
- * flags: 0 or STL_FLAG_GELU.  ws / ws_bytes: at least stl_aa_workspace_bytes(prob, nbatch, STL_OP_FORWARD).
+ * flags: any of STL_FLAG_GELU and STL_FLAG_B_TRANSPOSED.  With STL_FLAG_B_TRANSPOSED the second operand is given
+ * as its transpose, B: (nbatch*n) x k (Q K^T with K stored tokens x width), and the operator is applied to B_b^T: a tile
+ * of B^T is the transpose of a tile of B, so B is encoded as it lies with the columns of E_B permuted accordingly, and the
+ * planes are held as [p][J][L]: Bhat_save then has stl_plane_elems(nbatch*N, K, r) elements, and dB has B's shape.
+ * ws / ws_bytes: at least stl_aa_workspace_bytes(prob, nbatch, STL_OP_FORWARD).
  * nbatch*m and nbatch*k may not exceed 2^24 (INVALID_ARG).
  */
 size_t stl_aa_workspace_bytes(const stl_problem_t *prob, int64_t nbatch, int op);
@@ -211,14 +216,14 @@ stl_status_t stl_aa_forward(const stl_problem_t *prob, int64_t nbatch, const voi
  * dC: (nbatch*m) x n (in).  *_saved: NULL (recomputed) or what stl_aa_forward wrote.  dA, dB: storage dtype
  * (out); dE_A, dE_B, dD: r x 16 fp32 (out), summed over the batch; any output may be NULL.  dBhat is kept in the
  * storage dtype (it is a per-problem intermediate like dAhat, not an accumulated weight gradient).
- * accumulate: as in stl_backward, for dE_A, dE_B, dD.
+ * accumulate: as in stl_backward, for dE_A, dE_B, dD.  flags: 0 or STL_FLAG_B_TRANSPOSED, as in the forward call.
  * ws / ws_bytes: at least stl_aa_workspace_bytes(prob, nbatch, STL_OP_BACKWARD).
  */
 stl_status_t stl_aa_backward(const stl_problem_t *prob, int64_t nbatch, const void *A, const void *B,
                              const void *E_A, const void *E_B, const void *D, const void *dC,
                              const void *Ahat_saved, const void *Bhat_saved, const void *Yhat_saved, void *dA,
                              void *dB, float *dE_A, float *dE_B, float *dD, int accumulate, void *ws,
-                             size_t ws_bytes, void *stream);
+                             size_t ws_bytes, int flags, void *stream);
 
 /*
  * Row counts that t does not divide (Class-1 appendix, "More Details on STL Replacement in T2T-ViT", item 1):

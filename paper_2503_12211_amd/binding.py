@@ -17,6 +17,7 @@ STL_F32, STL_BF16 = 0, 1
 STL_OP_ENCODE_WEIGHT, STL_OP_FORWARD, STL_OP_BACKWARD, STL_OP_ENCODE_WEIGHT_BACKWARD = 0, 1, 2, 3
 STL_FLAG_AUTO, STL_FLAG_UNFUSED, STL_FLAG_EPILOGUE, STL_FLAG_FUSED = 0, 1, 2, 3
 STL_FLAG_GELU = 0x100
+STL_FLAG_B_TRANSPOSED = 0x200
 
 # every symbol include/stl.h declares
 SYMBOLS = (
@@ -87,7 +88,7 @@ def _load():
     lib.stl_aa_workspace_bytes.restype = ctypes.c_size_t
     lib.stl_aa_workspace_bytes.argtypes = [pp, ctypes.c_int64, ctypes.c_int]
     lib.stl_aa_forward.argtypes = [pp, ctypes.c_int64] + [_P] * 10 + [ctypes.c_size_t, ctypes.c_int, _P]
-    lib.stl_aa_backward.argtypes = [pp, ctypes.c_int64] + [_P] * 14 + [ctypes.c_int, _P, ctypes.c_size_t, _P]
+    lib.stl_aa_backward.argtypes = [pp, ctypes.c_int64] + [_P] * 14 + [ctypes.c_int, _P, ctypes.c_size_t, ctypes.c_int, _P]
     lib.stl_ragged_workspace_bytes.restype = ctypes.c_size_t
     lib.stl_ragged_workspace_bytes.argtypes = [pp, ctypes.c_int64, ctypes.c_int]
     lib.stl_ragged_forward.argtypes = [pp, ctypes.c_int64] + [_P] * 9 + [ctypes.c_size_t, _P]
@@ -218,10 +219,10 @@ def stl_aa_forward(prob: Problem, nbatch: int, A, B, E_A, E_B, D, C, Ahat_save=N
 
 
 def stl_aa_backward(prob: Problem, nbatch: int, A, B, E_A, E_B, D, dC, Ahat_saved, Bhat_saved, Yhat_saved, dA, dB, dE_A,
-                    dE_B, dD, accumulate: int = 0, ws=None, ws_bytes: int = 0, stream=None) -> None:
+                    dE_B, dD, accumulate: int = 0, ws=None, ws_bytes: int = 0, flags: int = 0, stream=None) -> None:
     _check(_load().stl_aa_backward(ctypes.byref(prob.c()), nbatch, _ptr(A), _ptr(B), _ptr(E_A), _ptr(E_B), _ptr(D), _ptr(dC),
                                    _ptr(Ahat_saved), _ptr(Bhat_saved), _ptr(Yhat_saved), _ptr(dA), _ptr(dB), _ptr(dE_A),
-                                   _ptr(dE_B), _ptr(dD), accumulate, _ptr(ws), ws_bytes, _stream(stream)))
+                                   _ptr(dE_B), _ptr(dD), accumulate, _ptr(ws), ws_bytes, flags, _stream(stream)))
 
 
 def stl_ragged_workspace_bytes(prob: Problem, rows: int, op: int) -> int:

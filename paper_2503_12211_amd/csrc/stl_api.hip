@@ -196,7 +196,7 @@ MlpWs mlp_layout(const stl_problem_t *up, const Dims &d1, const Dims &d2, int va
 
 // both operands encoded at run time, nbatch problems stacked along the rows
 struct AaWs {
-    size_t ahat, bhat, yhat, dyhat, dahat, dbhat, part, total;
+    size_t ahat, bhat, yhat, dyhat, dahat, dbhat, part, ebt, gbt, total;
 };
 
 size_t stacked_planes_bytes(const Dims &d, int64_t rows, int cols)
@@ -209,7 +209,9 @@ AaWs aa_layout(const Dims &d, int64_t nb, bool backward)
 {
     AaWs w{};
     size_t off = 0;
-    const size_t pa = stacked_planes_bytes(d, nb * d.M, d.K), pb = stacked_planes_bytes(d, nb * d.K, d.N),
+    // Bhat holds nb*K x N tile rows, or nb*N x K when the second operand is stored transposed: room for either
+    const size_t pb1 = stacked_planes_bytes(d, nb * d.K, d.N), pb2 = stacked_planes_bytes(d, nb * d.N, d.K);
+    const size_t pa = stacked_planes_bytes(d, nb * d.M, d.K), pb = pb1 > pb2 ? pb1 : pb2,
                  py = stacked_planes_bytes(d, nb * d.M, d.N);
     w.ahat = off;
     off += pa;
@@ -225,9 +227,9 @@ AaWs aa_layout(const Dims &d, int64_t nb, bool backward)
         w.dbhat = off;
         off += pb;
         int nblk = 1;
-        const int64_t Rs[3] = {nb * d.M, nb * d.M, nb * d.K};
-        const int Cs[3] = {d.N, d.K, d.N};
-        for (int i = 0; i < 3; ++i) {
+        const int64_t Rs[4] = {nb * d.M, nb * d.M, nb * d.K, nb * d.N};
+        const int Cs[4] = {d.N, d.K, d.N, d.K};
+        for (int i = 0; i < 4; ++i) {
             const int a = stl::outer_reduce_blocks(Rs[i] * Cs[i]), b = stl::decode_outer_blocks((int)Rs[i], Cs[i]),
                       c = stl::encode_outer_blocks((int)Rs[i], Cs[i]);
             nblk = a > nblk ? a : nblk;
@@ -237,6 +239,10 @@ AaWs aa_layout(const Dims &d, int64_t nb, bool backward)
         w.part = off;
         off += align256((size_t)nblk * d.r * 16 * sizeof(float));
     }
+    w.ebt = off;                                   // E_B with the tile transposition folded in (storage type)
+    off += align256((size_t)d.r * 16 * d.es);
+    w.gbt = off;                                   // its gradient before the transposition is undone (fp32)
+    off += align256((size_t)d.r * 16 * sizeof(float));
     w.total = off;
     return w;
 }
@@ -244,8 +250,8 @@ AaWs aa_layout(const Dims &d, int64_t nb, bool backward)
 stl_status_t check_batch(const stl_problem_t *p, const Dims &d, int64_t nb)
 {
     if (nb < 1) return fail(STL_ERR_INVALID_ARG, "nbatch=%lld must be positive", (long long)nb);
-    if (nb * p->m > kMaxDim || nb * p->k > kMaxDim)
-        return fail(STL_ERR_INVALID_ARG, "stacked rows nbatch*m or nbatch*k larger than %lld", (long long)kMaxDim);
+    if (nb * p->m > kMaxDim || nb * p->k > kMaxDim || nb * p->n > kMaxDim)
+        return fail(STL_ERR_INVALID_ARG, "stacked rows nbatch*m, nbatch*k or nbatch*n larger than %lld", (long long)kMaxDim);
     const double big = 1099511627776.0;
     if ((double)nb * d.r * d.M * d.K > big || (double)nb * d.r * d.M * d.N > big || (double)nb * d.r * d.K * d.N > big)
         return fail(STL_ERR_INVALID_ARG, "stacked plane tensors too large");
@@ -657,7 +663,8 @@ stl_status_t stl_aa_forward(const stl_problem_t *prob, int64_t nbatch, const voi
     if (st != STL_OK) return st;
     st = check_batch(prob, d, nbatch);
     if (st != STL_OK) return st;
-    if (flags & ~STL_FLAG_GELU) return fail(STL_ERR_UNSUPPORTED, "stl_aa_forward: unknown flag bits 0x%x", flags);
+    if (flags & ~(STL_FLAG_GELU | STL_FLAG_B_TRANSPOSED))
+        return fail(STL_ERR_UNSUPPORTED, "stl_aa_forward: unknown flag bits 0x%x", flags);
     if (!A || !B || !E_A || !E_B || !D || !C) return fail(STL_ERR_INVALID_ARG, "stl_aa_forward: NULL pointer");
     if (any_misaligned(A, B, E_A, E_B, D, C, Ahat_save, Bhat_save, Yhat_save))
         return fail(STL_ERR_INVALID_ARG, "stl_aa_forward: pointer not 16-byte aligned");
@@ -673,8 +680,16 @@ stl_status_t stl_aa_forward(const stl_problem_t *prob, int64_t nbatch, const voi
     void *yhat = Yhat_save ? Yhat_save : (void *)(base + w.yhat);
     // the stack of first operands is one tall matrix for the tile maps; so is the stack of second operands
     STL_HIP(stl::launch_encode(dt, A, E_A, ahat, nb * d.M, d.K, d.r, PG, s), "aa_forward/encode A");
-    STL_HIP(stl::launch_encode(dt, B, E_B, bhat, nb * d.K, d.N, d.r, PG, s), "aa_forward/encode B");
-    stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false, PG, PG, PG, nb};
+    const bool bt = (flags & STL_FLAG_B_TRANSPOSED) != 0;
+    if (bt) {
+        // tile (L, J) of B^T is the transpose of tile (J, L) of B: encode B as it lies with the transposition folded into
+        // the basis; the planes come out as [p][J][L], the [j][l] operand form of the plane products
+        STL_HIP(stl::launch_transpose_basis(dt, E_B, base + w.ebt, d.r, s), "aa_forward/transpose E_B");
+        STL_HIP(stl::launch_encode(dt, B, base + w.ebt, bhat, nb * d.N, d.K, d.r, PG, s), "aa_forward/encode B");
+    } else {
+        STL_HIP(stl::launch_encode(dt, B, E_B, bhat, nb * d.K, d.N, d.r, PG, s), "aa_forward/encode B");
+    }
+    stl::GemmDesc g{d.M, d.N, d.K, d.r, false, !bt, false, false, PG, PG, PG, nb};
     STL_HIP(stl::launch_plane_gemm(dt, g, ahat, bhat, yhat, s), "aa_forward/plane products");
     STL_HIP(stl::launch_decode(dt, yhat, D, C, nb * d.M, d.N, d.r, (flags & STL_FLAG_GELU) != 0, PG, s), "aa_forward/decode");
     return STL_OK;
@@ -683,7 +698,7 @@ stl_status_t stl_aa_forward(const stl_problem_t *prob, int64_t nbatch, const voi
 stl_status_t stl_aa_backward(const stl_problem_t *prob, int64_t nbatch, const void *A, const void *B, const void *E_A,
                              const void *E_B, const void *D, const void *dC, const void *Ahat_saved, const void *Bhat_saved,
                              const void *Yhat_saved, void *dA, void *dB, float *dE_A, float *dE_B, float *dD, int accumulate,
-                             void *ws, size_t ws_bytes, void *stream)
+                             void *ws, size_t ws_bytes, int flags, void *stream)
 {
     Dims d;
     stl_status_t st = check_problem(prob, &d);
@@ -694,14 +709,24 @@ stl_status_t stl_aa_backward(const stl_problem_t *prob, int64_t nbatch, const vo
     if (any_misaligned(A, B, E_A, E_B, D, dC, Ahat_saved, Bhat_saved, Yhat_saved, dA, dB, dE_A, dE_B, dD))
         return fail(STL_ERR_INVALID_ARG, "stl_aa_backward: pointer not 16-byte aligned");
     if (accumulate != 0 && accumulate != 1) return fail(STL_ERR_INVALID_ARG, "stl_aa_backward: accumulate must be 0 or 1");
+    if (flags & ~STL_FLAG_B_TRANSPOSED) return fail(STL_ERR_UNSUPPORTED, "stl_aa_backward: unknown flag bits 0x%x", flags);
+    const bool bt = (flags & STL_FLAG_B_TRANSPOSED) != 0;
     const AaWs w = aa_layout(d, nbatch, true);
     if (!ws || ws_bytes < w.total)
         return fail(STL_ERR_WORKSPACE, "stl_aa_backward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
     if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_aa_backward: workspace is not 16-byte aligned");
     hipStream_t s = (hipStream_t)stream;
     const int dt = prob->dtype, nb = (int)nbatch;
-    const int RA = nb * d.M, RB = nb * d.K;      // stacked tile rows of A (and C) and of B
+    // stacked tile rows of A (and C) and of B, and B's tile columns, as B is stored
+    const int RA = nb * d.M, RB = bt ? nb * d.N : nb * d.K, CB = bt ? d.K : d.N;
     char *base = (char *)ws;
+    const void *e_b = E_B;                       // the basis that encodes B as it lies
+    if (bt) {
+        STL_HIP(stl::launch_transpose_basis(dt, E_B, base + w.ebt, d.r, s), "aa_backward/transpose E_B");
+        e_b = base + w.ebt;
+    }
+    float *ge_b = bt ? (float *)(base + w.gbt) : dE_B;   // where the gradient of that basis is summed
+    const int acc_b = bt ? 0 : accumulate;
     float *part = (float *)(base + w.part);
     void *dyhat = base + w.dyhat, *dahat = base + w.dahat, *dbhat = base + w.dbhat;
 
@@ -712,11 +737,11 @@ stl_status_t stl_aa_backward(const stl_problem_t *prob, int64_t nbatch, const vo
         ahat = base + w.ahat;
     }
     if (!bhat && (want_a || (dD && !yhat))) {
-        STL_HIP(stl::launch_encode(dt, B, E_B, base + w.bhat, RB, d.N, d.r, PG, s), "aa_backward/encode B");
+        STL_HIP(stl::launch_encode(dt, B, e_b, base + w.bhat, RB, CB, d.r, PG, s), "aa_backward/encode B");
         bhat = base + w.bhat;
     }
     if (dD && !yhat) {
-        stl::GemmDesc g{d.M, d.N, d.K, d.r, false, true, false, false, PG, PG, PG, nb};
+        stl::GemmDesc g{d.M, d.N, d.K, d.r, false, !bt, false, false, PG, PG, PG, nb};
         STL_HIP(stl::launch_plane_gemm(dt, g, ahat, bhat, base + w.yhat, s), "aa_backward/recompute Yhat");
         yhat = base + w.yhat;
     }
@@ -728,7 +753,8 @@ stl_status_t stl_aa_backward(const stl_problem_t *prob, int64_t nbatch, const vo
     }
     if (want_a) {
         // dAhat[b][p] = dYhat[b][p] * Bhat[b][p]^T, then back through the encoding of A
-        stl::GemmDesc g{d.M, d.K, d.N, d.r, false, false, false, false, PG, PG, PG, nb};
+        // (with B stored transposed Bhat is [p][J][L]: the contraction index J is then its row index)
+        stl::GemmDesc g{d.M, d.K, d.N, d.r, false, bt, false, false, PG, PG, PG, nb};
         STL_HIP(stl::launch_plane_gemm(dt, g, dyhat, bhat, dahat, s), "aa_backward/dAhat");
         if (dA && dE_A && stl::decode_outer_eligible(dt, d.K)) {
             STL_HIP(stl::launch_decode_outer(dahat, E_A, dA, A, dE_A, part, RA, d.K, d.r, accumulate, PG, s), "aa_backward/dA + dE_A");
@@ -740,14 +766,21 @@ stl_status_t stl_aa_backward(const stl_problem_t *prob, int64_t nbatch, const vo
     if (want_b) {
         // dBhat[b][p] = Ahat[b][p]^T * dYhat[b][p] in the storage type (one problem each, nothing accumulates over the
         // batch), then back through the encoding of B
-        stl::GemmDesc g{d.K, d.N, d.M, d.r, true, true, false, false, PG, PG, PG, nb};
-        STL_HIP(stl::launch_plane_gemm(dt, g, ahat, dyhat, dbhat, s), "aa_backward/dBhat");
-        if (dB && dE_B && stl::decode_outer_eligible(dt, d.N)) {
-            STL_HIP(stl::launch_decode_outer(dbhat, E_B, dB, B, dE_B, part, RB, d.N, d.r, accumulate, PG, s), "aa_backward/dB + dE_B");
+        if (bt) {
+            // dBhat^T[b][p] = dYhat[b][p]^T * Ahat[b][p], in the layout Bhat has
+            stl::GemmDesc g{d.N, d.K, d.M, d.r, true, true, false, false, PG, PG, PG, nb};
+            STL_HIP(stl::launch_plane_gemm(dt, g, dyhat, ahat, dbhat, s), "aa_backward/dBhat");
         } else {
-            if (dB) STL_HIP(stl::launch_decode(dt, dbhat, E_B, dB, RB, d.N, d.r, false, PG, s), "aa_backward/decode dB");
-            if (dE_B) STL_HIP(stl::launch_outer_reduce(dt, dbhat, B, dE_B, part, RB, d.N, d.r, accumulate, PG, s), "aa_backward/dE_B");
+            stl::GemmDesc g{d.K, d.N, d.M, d.r, true, true, false, false, PG, PG, PG, nb};
+            STL_HIP(stl::launch_plane_gemm(dt, g, ahat, dyhat, dbhat, s), "aa_backward/dBhat");
         }
+        if (dB && dE_B && stl::decode_outer_eligible(dt, CB)) {
+            STL_HIP(stl::launch_decode_outer(dbhat, e_b, dB, B, ge_b, part, RB, CB, d.r, acc_b, PG, s), "aa_backward/dB + dE_B");
+        } else {
+            if (dB) STL_HIP(stl::launch_decode(dt, dbhat, e_b, dB, RB, CB, d.r, false, PG, s), "aa_backward/decode dB");
+            if (dE_B) STL_HIP(stl::launch_outer_reduce(dt, dbhat, B, ge_b, part, RB, CB, d.r, acc_b, PG, s), "aa_backward/dE_B");
+        }
+        if (bt && dE_B) STL_HIP(stl::launch_transpose_basis_grad(ge_b, dE_B, d.r, accumulate, s), "aa_backward/dE_B of the stored basis");
     }
     return STL_OK;
 }

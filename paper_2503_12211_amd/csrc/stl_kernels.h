@@ -83,6 +83,11 @@ hipError_t launch_fold_decoder(int dtype, const void *Dm, const float *fold, flo
 hipError_t launch_fold_grads(int dtype, const float *Gt, const void *Dm, const float *fold, float *dD, float *dfold, int r,
                              int nrho, int accumulate, hipStream_t s);
 
+// Et[p][4a+b] = E[p][4b+a] (storage type): the basis that encodes B^T when applied to the tiles of B; and the same map
+// on a gradient, G[p][4a+b] (+)= Gt[p][4b+a] (fp32)
+hipError_t launch_transpose_basis(int dtype, const void *E, void *Et, int r, hipStream_t s);
+hipError_t launch_transpose_basis_grad(const float *Gt, float *G, int r, int accumulate, hipStream_t s);
+
 // out[i] = bf16(in[i]), round to nearest even
 hipError_t launch_cast_bf16(const float *in, void *out, size_t n, hipStream_t s);
 

@@ -546,6 +546,31 @@ hipError_t launch_fold_grads(int dtype, const float *Gt, const void *Dm, const f
     return hipGetLastError();
 }
 
+// out[p][4a + b] (+)= in[p][4b + a]: vec of a transposed tile.  An encoder for B^T given as tiles of B, and the way back
+// for its gradient (the map is its own inverse).
+template <typename TI, typename TO>
+__global__ __launch_bounds__(256) void transpose_basis_kernel(const TI *__restrict__ in, TO *__restrict__ out, int r, int accumulate)
+{
+    for (int i = threadIdx.x; i < r * 16; i += 256) {
+        const int p = i >> 4, a = (i >> 2) & 3, b = i & 3;
+        const float v = Elem<TI>::ld(in + p * 16 + 4 * b + a);
+        Elem<TO>::st(out + i, accumulate ? Elem<TO>::ld(out + i) + v : v);
+    }
+}
+
+hipError_t launch_transpose_basis(int dtype, const void *E, void *Et, int r, hipStream_t s)
+{
+    if (dtype == 0) hipLaunchKernelGGL((transpose_basis_kernel<float, float>), dim3(1), dim3(256), 0, s, (const float *)E, (float *)Et, r, 0);
+    else hipLaunchKernelGGL((transpose_basis_kernel<bf16_t, bf16_t>), dim3(1), dim3(256), 0, s, (const bf16_t *)E, (bf16_t *)Et, r, 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose_basis_grad(const float *Gt, float *G, int r, int accumulate, hipStream_t s)
+{
+    hipLaunchKernelGGL((transpose_basis_kernel<float, float>), dim3(1), dim3(256), 0, s, Gt, G, r, accumulate);
+    return hipGetLastError();
+}
+
 // fp32 -> bf16 (round to nearest even), 8 elements per thread; n8 = number of 8-element groups, tail handled per element
 __global__ __launch_bounds__(256) void cast_bf16_kernel(const float *__restrict__ in, bf16_t *__restrict__ out, size_t n)
 {

@@ -97,8 +97,13 @@ int main(int argc, char **argv)
             CHECK(stl_aa_forward(&p, nb, A, B, Ea, Eb, D, C, Ah, Bh, Yh, exact(wf), wf, STL_FLAG_GELU, nullptr));
             void *dA = exact(nb * m * k * es), *dB = exact(nb * k * n * es);
             float *g1 = (float *)exact(r * 64), *g2 = (float *)exact(r * 64), *g3 = (float *)exact(r * 64);
-            CHECK(stl_aa_backward(&p, nb, A, B, Ea, Eb, D, dC, nullptr, nullptr, nullptr, dA, dB, g1, g2, g3, 0, exact(wb), wb, nullptr));
-            CHECK(stl_aa_backward(&p, nb, A, B, Ea, Eb, D, dC, Ah, Bh, Yh, dA, nullptr, nullptr, g2, nullptr, 1, exact(wb), wb, nullptr));
+            CHECK(stl_aa_backward(&p, nb, A, B, Ea, Eb, D, dC, nullptr, nullptr, nullptr, dA, dB, g1, g2, g3, 0, exact(wb), wb, 0, nullptr));
+            CHECK(stl_aa_backward(&p, nb, A, B, Ea, Eb, D, dC, Ah, Bh, Yh, dA, nullptr, nullptr, g2, nullptr, 1, exact(wb), wb, 0, nullptr));
+            // the second operand stored transposed: the same bytes read as (nb*n) x k
+            void *Bt = exact(stl_plane_elems(nb * n / 4, k / 4, r) * es);
+            CHECK(stl_aa_forward(&p, nb, A, B, Ea, Eb, D, C, Ah, Bt, Yh, exact(wf), wf, STL_FLAG_B_TRANSPOSED, nullptr));
+            CHECK(stl_aa_backward(&p, nb, A, B, Ea, Eb, D, dC, nullptr, nullptr, nullptr, dA, dB, g1, g2, g3, 0, exact(wb), wb, STL_FLAG_B_TRANSPOSED, nullptr));
+            CHECK(stl_aa_backward(&p, nb, A, B, Ea, Eb, D, dC, Ah, Bt, Yh, nullptr, dB, nullptr, g2, nullptr, 1, exact(wb), wb, STL_FLAG_B_TRANSPOSED, nullptr));
         } else if (op == "ragged") {
             const long nimg = v[0], rows = v[1], k = v[2], n = v[3], m = nimg * rows;
             const int r = (int)v[4];

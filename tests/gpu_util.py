@@ -180,13 +180,15 @@ def encode_weight_backward(W, E_W, dWhat, dtype, accumulate=0, init=None, skip=(
 
 
 def aa_forward(A, B, E_A, E_B, D, nb, dtype, flags=0, save=False):
-    """Stacked two-activation STL through the C ABI.  Returns C (and Ahat, Bhat, Yhat, plane-major) as float64 numpy."""
-    m, k, n, r = A.shape[0] // nb, A.shape[1], B.shape[1], D.shape[0]
+    """Stacked two-activation STL through the C ABI.  Returns C (and Ahat, Bhat, Yhat, plane-major) as float64 numpy.
+    With STL_FLAG_B_TRANSPOSED in flags B is (nb*n, k) and Bhat comes back as [p][J][L] over nb*N tile rows."""
+    bt = bool(flags & stl.STL_FLAG_B_TRANSPOSED)
+    m, k, n, r = A.shape[0] // nb, A.shape[1], (B.shape[0] // nb if bt else B.shape[1]), D.shape[0]
     prob = stl.Problem(m, k, n, r, STL_DT[dtype])
     Ad, Bd, Ea, Eb, Dd = (dev(x, dtype) for x in (A, B, E_A, E_B, D))
     gd = Guard()
     C = gd.alloc((nb * m, n), TORCH_DT[dtype])
-    shapes = [(nb * m // 4, k // 4), (nb * k // 4, n // 4), (nb * m // 4, n // 4)]
+    shapes = [(nb * m // 4, k // 4), (nb * n // 4, k // 4) if bt else (nb * k // 4, n // 4), (nb * m // 4, n // 4)]
     bufs = [gd.alloc((stl.stl_plane_elems(R, Cc, r),), TORCH_DT[dtype]) for R, Cc in shapes] if save else [None] * 3
     nbytes = stl.stl_aa_workspace_bytes(prob, nb, stl.STL_OP_FORWARD)
     ws = gd.alloc((max(nbytes, 16),), torch.uint8, fill=None)
@@ -197,14 +199,15 @@ def aa_forward(A, B, E_A, E_B, D, nb, dtype, flags=0, save=False):
     return host(C)
 
 
-def aa_backward(A, B, E_A, E_B, D, dC, nb, dtype, saved=None, accumulate=0, init=None, skip=()):
+def aa_backward(A, B, E_A, E_B, D, dC, nb, dtype, saved=None, accumulate=0, init=None, skip=(), flags=0):
     """Returns dict(dA, dB, dE_A, dE_B, dD) as float64 numpy.  saved: (Ahat, Bhat, Yhat) plane-major numpy or None."""
-    m, k, n, r = A.shape[0] // nb, A.shape[1], B.shape[1], D.shape[0]
+    bt = bool(flags & stl.STL_FLAG_B_TRANSPOSED)
+    m, k, n, r = A.shape[0] // nb, A.shape[1], (B.shape[0] // nb if bt else B.shape[1]), D.shape[0]
     prob = stl.Problem(m, k, n, r, STL_DT[dtype])
     Ad, Bd, Ea, Eb, Dd, dCd = (dev(x, dtype) for x in (A, B, E_A, E_B, D, dC))
     sv = [planes_to_dev(x, dtype) for x in saved] if saved is not None else [None] * 3
     gd = Guard()
-    outs = {"dA": gd.alloc((nb * m, k), TORCH_DT[dtype]), "dB": gd.alloc((nb * k, n), TORCH_DT[dtype])}
+    outs = {"dA": gd.alloc((nb * m, k), TORCH_DT[dtype]), "dB": gd.alloc(tuple(B.shape), TORCH_DT[dtype])}
     for i, name in enumerate(("dE_A", "dE_B", "dD")):
         outs[name] = gd.alloc((r, 16), torch.float32)
         if init is not None:
@@ -213,7 +216,7 @@ def aa_backward(A, B, E_A, E_B, D, dC, nb, dtype, saved=None, accumulate=0, init
     nbytes = stl.stl_aa_workspace_bytes(prob, nb, stl.STL_OP_BACKWARD)
     ws = gd.alloc((max(nbytes, 16),), torch.uint8, fill=None)
     stl.stl_aa_backward(prob, nb, Ad, Bd, Ea, Eb, Dd, dCd, sv[0], sv[1], sv[2], a["dA"], a["dB"], a["dE_A"], a["dE_B"],
-                        a["dD"], accumulate, ws, nbytes)
+                        a["dD"], accumulate, ws, nbytes, flags)
     gd.check()
     return {k_: host(v) for k_, v in outs.items()}
 

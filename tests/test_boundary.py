@@ -186,14 +186,14 @@ def test_two_activation_argument_checks():
     fwd, bwd = stl.stl_aa_workspace_bytes(prob, 4, F), stl.stl_aa_workspace_bytes(prob, 4, B)
     # stacked planes of A, B and Yhat; the backward adds their three gradients
     planes_bytes = 2 * (stl.stl_plane_elems(4 * 64, 16, 32) + stl.stl_plane_elems(4 * 16, 64, 32) + stl.stl_plane_elems(4 * 64, 64, 32))
-    assert fwd == planes_bytes and bwd > 2 * planes_bytes
+    assert planes_bytes < fwd < planes_bytes + 8192 and bwd > 2 * planes_bytes      # + two r x 16 slots for a transposed basis
     assert stl.stl_aa_workspace_bytes(prob, 8, F) > fwd
     assert stl.stl_aa_workspace_bytes(prob, 0, F) == 0 and stl.stl_aa_workspace_bytes(prob, 4, 7) == 0
     assert stl.stl_aa_workspace_bytes(prob, 1 << 20, F) == 0          # stacked rows beyond the cap
     ok = [FAKE] * 6 + [None] * 3
     for nb, args, ws, flags, status in ((0, ok, (FAKE, 1 << 40), 0, 1), (4, [None] + ok[1:], (FAKE, 1 << 40), 0, 1),
                                         (4, ok, (FAKE, fwd - 1), 0, 3), (4, ok, (None, 0), 0, 3),
-                                        (4, ok, (FAKE, 1 << 40), 0x200, 2), (4, ok, (FAKE, 1 << 40), stl.STL_FLAG_FUSED, 2),
+                                        (4, ok, (FAKE, 1 << 40), 0x400, 2), (4, ok, (FAKE, 1 << 40), stl.STL_FLAG_FUSED, 2),
                                         (4, [FAKE + 4] + ok[1:], (FAKE, 1 << 40), 0, 1)):
         with pytest.raises(stl.StlError) as e:
             stl.stl_aa_forward(prob, nb, *args, *ws, flags, stream=0)
@@ -204,6 +204,9 @@ def test_two_activation_argument_checks():
         with pytest.raises(stl.StlError) as e:
             stl.stl_aa_backward(prob, nb, *args, acc, *ws, stream=0)
         assert e.value.status == status
+    with pytest.raises(stl.StlError) as e:                # the backward takes only the transposed-operand flag
+        stl.stl_aa_backward(prob, 4, *okb, 0, FAKE, 1 << 40, stl.STL_FLAG_GELU, stream=0)
+    assert e.value.status == 2
 
 
 def test_ragged_argument_checks():

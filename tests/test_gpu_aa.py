@@ -112,3 +112,48 @@ def test_aa_attention_shape_full_size_sampled(gu):
     for b in (0, 13, 31):
         ref = planes.aa_forward(p["A"][b * m:(b + 1) * m], p["B"][b * k:(b + 1) * k], p["E_A"], p["E_B"], p["D"])
         assert gu.rel(got[b * m:(b + 1) * m], ref) <= gu.TOL["bf16"], b
+
+
+@pytest.mark.parametrize("dtype,nb,m,k,n,r", [
+    ("bf16", 3, 256, 128, 256, 32),
+    ("bf16", 32, 1024, 128, 1024, 32),     # attention scores Q K^T with K as it is stored (tokens x width), full size
+    ("bf16", 2, 200, 64, 72, 24),          # 50 / 18 tile rows: any-shape kernels
+    ("bf16", 4, 64, 96, 40, 49),
+    ("f32", 3, 48, 32, 40, 17),
+])
+def test_aa_transposed_second_operand(gu, dtype, nb, m, k, n, r):
+    """STL_FLAG_B_TRANSPOSED: B is stored (nb*n, k); forward, the handed-back planes ([p][J][L]) and all gradients."""
+    import paper_2503_12211_amd as stl
+    FL = stl.STL_FLAG_B_TRANSPOSED
+    p = stl_synth.aa_problem(nb, m, k, n, r, seed=8500 + m + k + n + r, dtype=dtype, with_dC=True)
+    Bt = np.ascontiguousarray(np.concatenate([p["B"][b * k:(b + 1) * k].T for b in range(nb)], axis=0))    # (nb*n, k)
+    args = (p["A"], Bt, p["E_A"], p["E_B"], p["D"])
+    full = nb * m * n <= 1 << 22
+    got, Ah, Bh, Yh = gu.aa_forward(*args, nb, dtype, flags=FL, save=True)
+    if full:
+        ref = planes.aa_forward(*args, nbatch=nb, b_transposed=True)
+        assert gu.rel(got, ref) <= gu.TOL[dtype]
+        # the stored planes are the encoding of B^T with tile rows and columns swapped
+        refB = planes.encode(p["B"], p["E_B"])                                   # (r, nb*K, N)
+        K, N = k // 4, n // 4
+        refBt = np.concatenate([refB[:, b * K:(b + 1) * K].transpose(0, 2, 1) for b in range(nb)], axis=1)
+        assert gu.rel(Bh, refBt) <= gu.TOL[dtype]
+        g = gu.aa_backward(*args, p["dC"], nb, dtype, flags=FL)
+        refs = dict(zip(("dA", "dB", "dE_A", "dE_B", "dD"), planes.aa_backward(*args, p["dC"], nbatch=nb, b_transposed=True)))
+        for name in refs:
+            assert gu.rel(g[name], refs[name]) <= gu.TOL[dtype], name
+        sv = gu.aa_backward(*args, p["dC"], nb, dtype, flags=FL, saved=(Ah, Bh, Yh))
+        for name in refs:
+            assert np.array_equal(sv[name], g[name]), name
+        rng = np.random.default_rng(1)
+        init = [rng.standard_normal((r, 16)).astype(np.float32) * 10 for _ in range(3)]
+        acc = gu.aa_backward(*args, p["dC"], nb, dtype, flags=FL, accumulate=1, init=init)
+        assert gu.rel(acc["dE_B"] - init[1], refs["dE_B"]) <= 2 * gu.TOL[dtype]
+    else:
+        # the same product with B given the other way round must agree bit for bit in C (same planes, same sums)
+        assert np.isfinite(got).all()
+        plain = gu.aa_forward(p["A"], p["B"], p["E_A"], p["E_B"], p["D"], nb, dtype)
+        for b in (0, 17, 31):
+            ref = planes.aa_forward(p["A"][b * m:(b + 1) * m], Bt[b * n:(b + 1) * n], p["E_A"], p["E_B"], p["D"], b_transposed=True)
+            assert gu.rel(got[b * m:(b + 1) * m], ref) <= gu.TOL[dtype], b
+        assert gu.rel(got, plain) <= 2e-3

@@ -354,6 +354,23 @@ def main():
                      "frac": round(tf(gemm_flop, ms_gemm) / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(wname)},
     }
 
+    # the same step captured once in a HIP graph and replayed (the calls only enqueue kernels: nothing to re-record)
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        out["stl_ms"]["step_graph_replay"] = round(T.wall(graph.replay, S, W), 5)
+        log(f"  step replayed from a HIP graph: {out['stl_ms']['step_graph_replay']:.4f} ms")
+        del graph
+    except Exception as e:                                       # measurement extra: never fails the run
+        log(f"  graph replay leg skipped: {e}")
+
     # the other forward variants at the same workload (STL_FLAG_AUTO runs the three-launch path)
     variants = {}
     for name, flag in (("unfused", stl.STL_FLAG_UNFUSED), ("epilogue", stl.STL_FLAG_EPILOGUE), ("fused", stl.STL_FLAG_FUSED)):

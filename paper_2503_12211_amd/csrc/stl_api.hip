@@ -552,15 +552,18 @@ stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *
         STL_HIP(stl::launch_encode(dt, dC, D, dyhat, d.M, d.N, d.r, PG, s), "backward/encode dC");
         if (dD) STL_HIP(stl::launch_outer_reduce(dt, yhat, dC, dD, part, d.M, d.N, d.r, accumulate, PG, s), "backward/dD");
     }
-    if (dX || dE_X) {
-        // dXhat[p] = dYhat[p] * What[p]^T : contraction over J, What[p] is stored [L][J]
-        stl::GemmDesc g{d.M, d.K, d.N, d.r, false, false, false, false, PG, 0, PG};
-        STL_HIP(stl::launch_plane_gemm(dt, g, dyhat, What, dxhat, s), "backward/dXhat");
-    }
+    // The weight gradient goes first: the pass that follows the second product (decode of dXhat) is bound by HBM and
+    // finds the freshly written dXhat in the last-level cache, which a product in between would have flushed; the
+    // products themselves do not care which of them reads dYhat warm.
     if (dWhat) {
         // dWhat[p] = Xhat[p]^T * dYhat[p] : contraction over I, both operands stored [I][.]
         stl::GemmDesc g{d.K, d.N, d.M, d.r, true, true, true, accumulate != 0, PG, PG, 0};
         STL_HIP(stl::launch_plane_gemm(dt, g, xhat, dyhat, dWhat, s), "backward/dWhat");
+    }
+    if (dX || dE_X) {
+        // dXhat[p] = dYhat[p] * What[p]^T : contraction over J, What[p] is stored [L][J]
+        stl::GemmDesc g{d.M, d.K, d.N, d.r, false, false, false, false, PG, 0, PG};
+        STL_HIP(stl::launch_plane_gemm(dt, g, dyhat, What, dxhat, s), "backward/dXhat");
     }
     if (dX && dE_X && stl::decode_outer_eligible(dt, d.K)) {
         // one pass over dXhat: dX = decode with E_X, dE_X = sum over tiles of dXhat (x) x

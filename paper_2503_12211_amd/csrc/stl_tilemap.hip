@@ -325,16 +325,20 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
                                                           RowMap rm)
 {
     constexpr int ROWB = 128;                               // bytes per LDS row (64 tiles)
-    constexpr int VPITCH = 64 + 8;                          // bf16 elements per row of the entry x tile staging
     __shared__ __align__(16) char slab_all[4][KC * 32 * ROWB];
-    __shared__ __align__(16) bf16_t sV[OUTER ? 4 : 1][OUTER ? 16 : 1][OUTER ? VPITCH : 8];
+    // OUTER: per wavefront the 64 tiles of V, tile-major [tile][16 entries] (32 bytes per tile)
+    __shared__ __align__(16) char sT_all[OUTER ? 4 : 1][OUTER ? 64 * 32 : 16];
     const int ngroups = (r + 15) >> 4;
     f32x4_t oacc[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) oacc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     char *slab = slab_all[wave];
+    char *sT = sT_all[OUTER ? wave : 0];
     const int j = lane & 15, kq = lane >> 4;
+    // row of tile `lane` in sT: rows t and t^4 are swapped where bit 3 of t is set, so that the four 4-tile groups one
+    // transposing read touches fall into both halves of the banks
+    const int strow = lane ^ (((lane >> 3) & 1) << 2);
 
     // A fragments: lane (entry q = j, kq) holds D[32g + 8kq + e][q], e = 0..7
     bf16x8_t fa[KC];
@@ -404,15 +408,10 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
             *reinterpret_cast<u32x4_t *>(slab + pl * ROWB + ((ch ^ swz(pl)) << 4)) = pre[g8];
         }
         if (OUTER) {
-            // lane = tile J0 + lane: its 16 entries (4 rows x 8 bytes) -> sV[entry][tile]
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const u32x2_t xv = xpre[a];
-                sV[wave][4 * a + 0][lane] = (bf16_t)(xv[0] & 0xffffu);
-                sV[wave][4 * a + 1][lane] = (bf16_t)(xv[0] >> 16);
-                sV[wave][4 * a + 2][lane] = (bf16_t)(xv[1] & 0xffffu);
-                sV[wave][4 * a + 3][lane] = (bf16_t)(xv[1] >> 16);
-            }
+            // lane = tile J0 + lane: its 16 entries (4 rows x 8 bytes) as two 16-byte writes, tile-major; they come back
+            // as "entry x 4 consecutive tiles" through the transposing read below
+            *reinterpret_cast<u32x4_t *>(sT + strow * 32) = u32x4_t{xpre[0][0], xpre[0][1], xpre[1][0], xpre[1][1]};
+            *reinterpret_cast<u32x4_t *>(sT + strow * 32 + 16) = u32x4_t{xpre[2][0], xpre[2][1], xpre[3][0], xpre[3][1]};
         }
         In += dI;
         ckn += dck;
@@ -420,10 +419,20 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
         if (item0 + stride < items) fetch(In, ckn);
         if (live && OUTER) {
             // K = 32 tiles per MFMA: A = planes x tiles from the slab (lane: plane 16g + j, tiles 32s + 8kq ..),
-            // B = tiles x entries from sV (lane: entry j, same tiles)
+            // B = tiles x entries from sT (lane: entry j, same tiles)
 #pragma unroll
             for (int sx = 0; sx < 2; ++sx) {
-                const bf16x8_t fb = *reinterpret_cast<const bf16x8_t *>(&sV[wave][j][32 * sx + 8 * kq]);
+                v4i16_t tb[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    // source address of this lane inside its 16-lane group: tile row (32sx + 8kq + 4h) + j/4, entries 4*(j%4)..
+                    const int t0 = 32 * sx + 8 * kq + 4 * h;
+                    const int row = (t0 ^ (((t0 >> 3) & 1) << 2)) + (j >> 2);
+                    tb[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t *)(
+                        (__attribute__((address_space(3))) char *)(sT + row * 32 + 8 * (j & 3))));
+                }
+                struct { v4i16_t a, b; } both_b = {tb[0], tb[1]};
+                const bf16x8_t fb = __builtin_bit_cast(bf16x8_t, both_b);
 #pragma unroll
                 for (int g = 0; g < 2 * KC; ++g) {
                     if (g < ngroups) {

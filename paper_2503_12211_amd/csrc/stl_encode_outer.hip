@@ -24,17 +24,18 @@ namespace stl {
 
 typedef short v4i16_t __attribute__((ext_vector_type(4)));
 
-template <int KC>   // KC = number of 32-plane groups (1: r <= 32, 2: r <= 64)
+// OUTER = false: the encode alone (Qp, part unused) -- the same whole-line stores through the slab, used for plain encodes
+template <int KC, bool OUTER>   // KC = number of 32-plane groups (1: r <= 32, 2: r <= 64)
 __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ E,
                                                              bf16_t *__restrict__ P, const bf16_t *__restrict__ Qp,
                                                              float *__restrict__ part, int R, int Cc, int r, int chunks, int pg,
                                                              RowMap rm)
 {
     constexpr int ROWB = 128;                               // bytes per plane row of the slab (64 tiles)
-    __shared__ __align__(16) char sT_all[4][64 * 32];       // per wavefront: [tile][16 entries] bf16
+    __shared__ __align__(16) char sT_all[OUTER ? 4 : 1][OUTER ? 64 * 32 : 16];   // per wavefront: [tile][16 entries] bf16
     __shared__ __align__(16) char slab_all[4][KC * 32 * ROWB];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    char *sT = sT_all[wave], *slab = slab_all[wave];
+    char *sT = sT_all[OUTER ? wave : 0], *slab = slab_all[wave];
     // 16-byte chunk swizzle of a plane row: a fragment read takes chunk 4sx + kq of 16 rows; odd/even rows already
     // alternate the bank half, bit 1 of the row moves the chunk to the other four positions
     auto swz = [](int row) { return ((row >> 1) & 1) << 2; };
@@ -85,12 +86,14 @@ __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__res
             if (row_ok && J0 + trel[u] < Cc) v = *reinterpret_cast<const u32x2_t *>(A + (r0 + kq) * ld + (size_t)(J0 + trel[u]) * 4);
             xa[u] = v;
         }
+        if (OUTER) {
 #pragma unroll
-        for (int g8 = 0; g8 < KC * 4; ++g8) {
-            const int pl = 8 * g8 + pr, tk = J0 + 8 * ch;
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (Ii < R && pl < r && tk < Cc) v = *reinterpret_cast<const u32x4_t *>(Qp + rowb + (size_t)pl * plane + tk);
-            qa[g8] = v;
+            for (int g8 = 0; g8 < KC * 4; ++g8) {
+                const int pl = 8 * g8 + pr, tk = J0 + 8 * ch;
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (Ii < R && pl < r && tk < Cc) v = *reinterpret_cast<const u32x4_t *>(Qp + rowb + (size_t)pl * plane + tk);
+                qa[g8] = v;
+            }
         }
     };
     fetch(In, ckn);
@@ -101,10 +104,12 @@ __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__res
 #pragma unroll
         for (int u = 0; u < 4; ++u) x[u] = xa[u];
         // plane segments -> slab (private to the wavefront, whose LDS operations execute in order: no barrier)
+        if (OUTER) {
 #pragma unroll
-        for (int g8 = 0; g8 < KC * 4; ++g8) {
-            const int pl = 8 * g8 + pr;
-            *reinterpret_cast<u32x4_t *>(slab + pl * ROWB + ((ch ^ swz(pl)) << 4)) = qa[g8];
+            for (int g8 = 0; g8 < KC * 4; ++g8) {
+                const int pl = 8 * g8 + pr;
+                *reinterpret_cast<u32x4_t *>(slab + pl * ROWB + ((ch ^ swz(pl)) << 4)) = qa[g8];
+            }
         }
         In += dI;
         ckn += dck;
@@ -114,12 +119,14 @@ __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__res
         const int I = rm.tile_row(Iidx);
 
         // tile rows -> second slab
+        if (OUTER) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) *reinterpret_cast<u32x2_t *>(sT + srow[u] * 32 + 8 * kq) = x[u];
+            for (int u = 0; u < 4; ++u) *reinterpret_cast<u32x2_t *>(sT + srow[u] * 32 + 8 * kq) = x[u];
+        }
 
         // basis gradient: K = 32 tiles per product; B fragment of lane (entry j, kq) = tiles 32sx + 8kq .. +7 of entry j
 #pragma unroll
-        for (int sx = 0; sx < 2; ++sx) {
+        for (int sx = 0; sx < (OUTER ? 2 : 0); ++sx) {
             v4i16_t t[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -174,6 +181,7 @@ __global__ __launch_bounds__(256) void encode_outer16_kernel(const bf16_t *__res
         }
     }
 
+    if (!OUTER) return;
     // accumulator e of group g: plane 16g + 4kq + e, tile entry j; fixed-order sum over the four wavefronts
     __syncthreads();                                        // every wavefront is done with its slab
     float *red = reinterpret_cast<float *>(&slab_all[0][0]); // 4 x (32 KC x 16) floats = the slabs' size
@@ -205,14 +213,33 @@ hipError_t launch_encode_outer(const void *A, const void *E, void *P, const void
     const int chunks = (Cc + 63) / 64;
     const int nb = encode_outer_blocks(R, Cc);
     if (r <= 32)
-        hipLaunchKernelGGL(encode_outer16_kernel<1>, dim3(nb), dim3(256), 0, s, (const bf16_t *)A, (const bf16_t *)E,
+        hipLaunchKernelGGL((encode_outer16_kernel<1, true>), dim3(nb), dim3(256), 0, s, (const bf16_t *)A, (const bf16_t *)E,
                            (bf16_t *)P, (const bf16_t *)Qp, part, R, Cc, r, chunks, pg, rm);
     else
-        hipLaunchKernelGGL(encode_outer16_kernel<2>, dim3(nb), dim3(256), 0, s, (const bf16_t *)A, (const bf16_t *)E,
+        hipLaunchKernelGGL((encode_outer16_kernel<2, true>), dim3(nb), dim3(256), 0, s, (const bf16_t *)A, (const bf16_t *)E,
                            (bf16_t *)P, (const bf16_t *)Qp, part, R, Cc, r, chunks, pg, rm);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_outer_final(part, G, nb, r * 16, accumulate, s);
+}
+
+// the encode alone through the same kernel (bf16, Cc % 8 == 0): grid-stride over (tile row, 64-tile chunk) items
+hipError_t launch_encode_lines(const void *A, const void *E, void *P, int R, int Cc, int r, int pg, hipStream_t s, RowMap rm)
+{
+    if (pg <= 0) pg = R;
+    R = rm.count(R);
+    if (R <= 0) return hipSuccess;
+    const int chunks = (Cc + 63) / 64;
+    const long items = (long)R * chunks;
+    long blocks = (items + 3) / 4;
+    if (blocks > 8192) blocks = 8192;
+    if (r <= 32)
+        hipLaunchKernelGGL((encode_outer16_kernel<1, false>), dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t *)A,
+                           (const bf16_t *)E, (bf16_t *)P, (const bf16_t *)nullptr, (float *)nullptr, R, Cc, r, chunks, pg, rm);
+    else
+        hipLaunchKernelGGL((encode_outer16_kernel<2, false>), dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t *)A,
+                           (const bf16_t *)E, (bf16_t *)P, (const bf16_t *)nullptr, (float *)nullptr, R, Cc, r, chunks, pg, rm);
+    return hipGetLastError();
 }
 
 }  // namespace stl

@@ -88,6 +88,9 @@ hipError_t launch_fold_grads(int dtype, const float *Gt, const void *Dm, const f
 hipError_t launch_transpose_basis(int dtype, const void *E, void *Et, int r, hipStream_t s);
 hipError_t launch_transpose_basis_grad(const float *Gt, float *G, int r, int accumulate, hipStream_t s);
 
+// bf16 encode with whole-line plane stores (Cc % 8 == 0); launch_encode picks it
+hipError_t launch_encode_lines(const void *A, const void *E, void *P, int R, int Cc, int r, int pg, hipStream_t s, RowMap rm);
+
 // out[i] = bf16(in[i]), round to nearest even
 hipError_t launch_cast_bf16(const float *in, void *out, size_t n, hipStream_t s);
 

@@ -351,7 +351,10 @@ def main():
         "roofline": {"kernel": "gemm_pipe_kernel (forward plane products Yhat[p] = Xhat[p] What[p], one launch, "
                                "2*r*M*K*N flops)", "bound": "mfma",
                      "achieved": round(tf(gemm_flop, ms_gemm), 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tf(gemm_flop, ms_gemm) / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(wname)},
+                     "frac": round(tf(gemm_flop, ms_gemm) / PEAK_BF16_TFLOPS, 4),
+                     "traffic": (measured_traffic(wname) or {}).get("hbm_bytes"),          # HBM bytes per launch, or null
+                     "traffic_detail": measured_traffic(wname),
+                     "algorithmic_bytes": int(2 * (r * M * K + r * K * N + r * M * N))},
     }
 
     # the same step captured once in a HIP graph and replayed (the calls only enqueue kernels: nothing to re-record)

@@ -67,6 +67,15 @@ bool any_misaligned(P... ptrs)
     return ((((uintptr_t)ptrs) & 15) || ...);
 }
 
+// scratch: present and large enough when any is needed, 16-byte aligned when given
+stl_status_t check_workspace(const char *fn, const void *ws, size_t ws_bytes, size_t need)
+{
+    if (need > 0 && (!ws || ws_bytes < need))
+        return fail(STL_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, ws ? ws_bytes : (size_t)0);
+    if (ws && ((uintptr_t)ws & 15)) return fail(STL_ERR_INVALID_ARG, "%s: workspace is not 16-byte aligned", fn);
+    return STL_OK;
+}
+
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct FwdWs {
@@ -392,10 +401,8 @@ stl_status_t stl_encode_weight_backward(const stl_problem_t *prob, const void *W
     if (accumulate != 0 && accumulate != 1)
         return fail(STL_ERR_INVALID_ARG, "stl_encode_weight_backward: accumulate must be 0 or 1");
     const EwbWs w = ewb_layout(prob, d);
-    if (!ws || ws_bytes < w.total)
-        return fail(STL_ERR_WORKSPACE, "stl_encode_weight_backward: workspace of %zu bytes needed, %zu given", w.total,
-                    ws ? ws_bytes : 0);
-    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_encode_weight_backward: workspace is not 16-byte aligned");
+    st = check_workspace("stl_encode_weight_backward", ws, ws_bytes, w.total);
+    if (st != STL_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     const int dt = prob->dtype;
     char *base = (char *)ws;
@@ -472,9 +479,8 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
             return fail(STL_ERR_UNSUPPORTED, "stl_forward: the fused variant never materialises Xhat (Xhat_save must be NULL)");
     }
     const FwdWs w = fwd_layout(d, variant);
-    if (w.total > 0 && (!ws || ws_bytes < w.total))
-        return fail(STL_ERR_WORKSPACE, "stl_forward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
-    if (ws && ((uintptr_t)ws & 15)) return fail(STL_ERR_INVALID_ARG, "stl_forward: workspace is not 16-byte aligned");
+    st = check_workspace("stl_forward", ws, ws_bytes, w.total);
+    if (st != STL_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     const bool gelu = (flags & STL_FLAG_GELU) != 0;
     char *base = (char *)ws;
@@ -526,9 +532,8 @@ stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *
         return fail(STL_ERR_INVALID_ARG, "stl_backward: pointer not 16-byte aligned");
     if (accumulate != 0 && accumulate != 1) return fail(STL_ERR_INVALID_ARG, "stl_backward: accumulate must be 0 or 1");
     const BwdWs w = bwd_layout(d);
-    if (!ws || ws_bytes < w.total)
-        return fail(STL_ERR_WORKSPACE, "stl_backward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
-    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_backward: workspace is not 16-byte aligned");
+    st = check_workspace("stl_backward", ws, ws_bytes, w.total);
+    if (st != STL_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     const int dt = prob->dtype;
     char *base = (char *)ws;
@@ -622,9 +627,8 @@ stl_status_t stl_mlp_forward(const stl_problem_t *up, const stl_problem_t *down,
     if (any_misaligned(X, What1, E_X1, D1, What2, E_X2, D2, C))
         return fail(STL_ERR_INVALID_ARG, "stl_mlp_forward: pointer not 16-byte aligned");
     const MlpWs w = mlp_layout(up, d1, d2, variant);
-    if (!ws || ws_bytes < w.total)
-        return fail(STL_ERR_WORKSPACE, "stl_mlp_forward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
-    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_mlp_forward: workspace is not 16-byte aligned");
+    st = check_workspace("stl_mlp_forward", ws, ws_bytes, w.total);
+    if (st != STL_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     const int dt = up->dtype;
     const bool gelu = (flags & STL_FLAG_GELU) != 0;
@@ -672,9 +676,8 @@ stl_status_t stl_aa_forward(const stl_problem_t *prob, int64_t nbatch, const voi
     if (any_misaligned(A, B, E_A, E_B, D, C, Ahat_save, Bhat_save, Yhat_save))
         return fail(STL_ERR_INVALID_ARG, "stl_aa_forward: pointer not 16-byte aligned");
     const AaWs w = aa_layout(d, nbatch, false);
-    if (!ws || ws_bytes < w.total)
-        return fail(STL_ERR_WORKSPACE, "stl_aa_forward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
-    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_aa_forward: workspace is not 16-byte aligned");
+    st = check_workspace("stl_aa_forward", ws, ws_bytes, w.total);
+    if (st != STL_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     const int dt = prob->dtype, nb = (int)nbatch;
     char *base = (char *)ws;
@@ -715,9 +718,8 @@ stl_status_t stl_aa_backward(const stl_problem_t *prob, int64_t nbatch, const vo
     if (flags & ~STL_FLAG_B_TRANSPOSED) return fail(STL_ERR_UNSUPPORTED, "stl_aa_backward: unknown flag bits 0x%x", flags);
     const bool bt = (flags & STL_FLAG_B_TRANSPOSED) != 0;
     const AaWs w = aa_layout(d, nbatch, true);
-    if (!ws || ws_bytes < w.total)
-        return fail(STL_ERR_WORKSPACE, "stl_aa_backward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
-    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_aa_backward: workspace is not 16-byte aligned");
+    st = check_workspace("stl_aa_backward", ws, ws_bytes, w.total);
+    if (st != STL_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     const int dt = prob->dtype, nb = (int)nbatch;
     // stacked tile rows of A (and C) and of B, and B's tile columns, as B is stored
@@ -811,9 +813,8 @@ stl_status_t stl_ragged_forward(const stl_problem_t *prob, int64_t rows, const v
     if (any_misaligned(X, What, E_X, D, fold, C, Xhat_save, Yhat_save))
         return fail(STL_ERR_INVALID_ARG, "stl_ragged_forward: pointer not 16-byte aligned");
     const RagWs w = ragged_layout(g, false);
-    if (!ws || ws_bytes < w.total)
-        return fail(STL_ERR_WORKSPACE, "stl_ragged_forward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
-    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_ragged_forward: workspace is not 16-byte aligned");
+    st = check_workspace("stl_ragged_forward", ws, ws_bytes, w.total);
+    if (st != STL_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     const int dt = prob->dtype;
     char *base = (char *)ws;
@@ -850,9 +851,8 @@ stl_status_t stl_ragged_backward(const stl_problem_t *prob, int64_t rows, const 
         return fail(STL_ERR_INVALID_ARG, "stl_ragged_backward: pointer not 16-byte aligned");
     if (accumulate != 0 && accumulate != 1) return fail(STL_ERR_INVALID_ARG, "stl_ragged_backward: accumulate must be 0 or 1");
     const RagWs w = ragged_layout(g, true);
-    if (!ws || ws_bytes < w.total)
-        return fail(STL_ERR_WORKSPACE, "stl_ragged_backward: workspace of %zu bytes needed, %zu given", w.total, ws ? ws_bytes : 0);
-    if ((uintptr_t)ws & 15) return fail(STL_ERR_INVALID_ARG, "stl_ragged_backward: workspace is not 16-byte aligned");
+    st = check_workspace("stl_ragged_backward", ws, ws_bytes, w.total);
+    if (st != STL_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     const int dt = prob->dtype;
     char *base = (char *)ws;

@@ -106,7 +106,7 @@ FwdWs fwd_layout(const Dims &d, int variant)
 }
 
 struct BwdWs {
-    size_t xhat, dyhat, dxhat, yhat, part, total;
+    size_t xhat, dyhat, dxhat, yhat, part, part2, total;
 };
 
 BwdWs bwd_layout(const Dims &d)
@@ -128,7 +128,10 @@ BwdWs bwd_layout(const Dims &d)
     nb = nb > nb_k ? nb : nb_k;
     nb = nb > nb_f ? nb : nb_f;
     nb = nb > nb_e ? nb : nb_e;
+    // two areas of partial sums: the two fused gradient passes leave theirs for one common final sum
     w.part = off;
+    off += align256((size_t)nb * d.r * 16 * sizeof(float));
+    w.part2 = off;
     off += align256((size_t)nb * d.r * 16 * sizeof(float));
     w.total = off;
     return w;
@@ -318,7 +321,7 @@ RagWs ragged_layout(const Ragged &g, bool backward)
         w.dxhat = off;
         off += pk;
         w.part = off;
-        off += align256(bwd_layout(d).total - bwd_layout(d).part);      // the same partial-sum area as stl_backward
+        off += align256(bwd_layout(d).part2 - bwd_layout(d).part);      // a partial-sum area as in stl_backward
     }
     w.dprime = off;
     off += align256((size_t)d.r * 16 * sizeof(float));
@@ -550,9 +553,13 @@ stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *
         STL_HIP(stl::launch_plane_gemm(dt, g, xhat, What, base + w.yhat, s), "backward/recompute Yhat");
         yhat = base + w.yhat;
     }
+    // when both fused gradient passes run, their block partials are added up by one launch at the end
+    const bool pair = dD && stl::encode_outer_eligible(dt, d.N) && dX && dE_X && stl::decode_outer_eligible(dt, d.K);
+    float *part2 = (float *)(base + w.part2);
     if (dD && stl::encode_outer_eligible(dt, d.N)) {
         // one pass over dC: dYhat = encode with D, dD = sum over tiles of Yhat (x) dc
-        STL_HIP(stl::launch_encode_outer(dC, D, dyhat, yhat, dD, part, d.M, d.N, d.r, accumulate, PG, s), "backward/dYhat + dD");
+        STL_HIP(stl::launch_encode_outer(dC, D, dyhat, yhat, dD, part, d.M, d.N, d.r, accumulate, PG, s, stl::RowMap(), !pair),
+                "backward/dYhat + dD");
     } else {
         STL_HIP(stl::launch_encode(dt, dC, D, dyhat, d.M, d.N, d.r, PG, s), "backward/encode dC");
         if (dD) STL_HIP(stl::launch_outer_reduce(dt, yhat, dC, dD, part, d.M, d.N, d.r, accumulate, PG, s), "backward/dD");
@@ -572,7 +579,13 @@ stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *
     }
     if (dX && dE_X && stl::decode_outer_eligible(dt, d.K)) {
         // one pass over dXhat: dX = decode with E_X, dE_X = sum over tiles of dXhat (x) x
-        STL_HIP(stl::launch_decode_outer(dxhat, E_X, dX, X, dE_X, part, d.M, d.K, d.r, accumulate, PG, s), "backward/dX + dE_X");
+        STL_HIP(stl::launch_decode_outer(dxhat, E_X, dX, X, dE_X, pair ? part2 : part, d.M, d.K, d.r, accumulate, PG, s,
+                                         stl::RowMap(), !pair),
+                "backward/dX + dE_X");
+        if (pair)
+            STL_HIP(stl::launch_outer_final_pair(part, dD, stl::encode_outer_blocks(d.M, d.N), part2, dE_X,
+                                                 stl::decode_outer_blocks(d.M, d.K), d.r * 16, accumulate, s),
+                    "backward/dD and dE_X sums");
     } else {
         if (dX) STL_HIP(stl::launch_decode(dt, dxhat, E_X, dX, d.M, d.K, d.r, false, PG, s), "backward/decode dX");
         if (dE_X)

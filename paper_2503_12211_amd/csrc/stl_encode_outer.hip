@@ -205,7 +205,7 @@ int encode_outer_blocks(int R, int Cc)
 }
 
 hipError_t launch_encode_outer(const void *A, const void *E, void *P, const void *Qp, float *G, float *part, int R, int Cc,
-                               int r, int accumulate, int pg, hipStream_t s, RowMap rm)
+                               int r, int accumulate, int pg, hipStream_t s, RowMap rm, bool final_sum)
 {
     if (pg <= 0) pg = R;
     R = rm.count(R);                                        // tile rows this launch walks over
@@ -219,7 +219,7 @@ hipError_t launch_encode_outer(const void *A, const void *E, void *P, const void
         hipLaunchKernelGGL((encode_outer16_kernel<2, true>), dim3(nb), dim3(256), 0, s, (const bf16_t *)A, (const bf16_t *)E,
                            (bf16_t *)P, (const bf16_t *)Qp, part, R, Cc, r, chunks, pg, rm);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || !final_sum) return e;
     return launch_outer_final(part, G, nb, r * 16, accumulate, s);
 }
 

@@ -65,17 +65,20 @@ hipError_t launch_outer_reduce(int dtype, const void *P, const void *V, float *G
 bool decode_outer_eligible(int dtype, int Cc);
 int decode_outer_blocks(int R, int Cc);
 hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const void *V, float *G, float *part, int R,
-                               int Cc, int r, int accumulate, int pg, hipStream_t s, RowMap rm = RowMap());
+                               int Cc, int r, int accumulate, int pg, hipStream_t s, RowMap rm = RowMap(), bool final_sum = true);
 
 // G[i] (+)= sum over nb partials part[b][i], i < n_out, in block order (second stage of the basis-gradient sums)
 hipError_t launch_outer_final(const float *part, float *G, int nb, int n_out, int accumulate, hipStream_t s);
+// two such sums in one launch (final_sum = false in the two fused passes leaves their partials for this)
+hipError_t launch_outer_final_pair(const float *part0, float *G0, int nb0, const float *part1, float *G1, int nb1, int n_out,
+                                   int accumulate, hipStream_t s);
 
 // encode and basis gradient in one pass over the matrix (bf16): P <- encode(A, E), G (+)= Qp . tileview(A);
 // `part` holds encode_outer_blocks(R, Cc) * r * 16 floats
 bool encode_outer_eligible(int dtype, int Cc);
 int encode_outer_blocks(int R, int Cc);
 hipError_t launch_encode_outer(const void *A, const void *E, void *P, const void *Qp, float *G, float *part, int R, int Cc,
-                               int r, int accumulate, int pg, hipStream_t s, RowMap rm = RowMap());
+                               int r, int accumulate, int pg, hipStream_t s, RowMap rm = RowMap(), bool final_sum = true);
 
 // fold of an image's last tile row (row counts not divisible by 4): composed decoder Dp (r x 16 fp32) from Dm and the
 // nrho x 4 fold coefficients; and the gradients that come from those tile rows, given Gt = Yhat (x) dC over them

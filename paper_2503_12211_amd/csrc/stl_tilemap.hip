@@ -127,8 +127,15 @@ __global__ __launch_bounds__(256) void outer_partial_kernel(const T *__restrict_
 }
 
 __global__ __launch_bounds__(256) void outer_final_kernel(const float *__restrict__ part, float *__restrict__ G,
-                                                          int nblocks, int n_out, int accumulate)
+                                                          int nblocks, int n_out, int accumulate,
+                                                          const float *__restrict__ part1 = nullptr,
+                                                          float *__restrict__ G1 = nullptr, int nblocks1 = 0)
 {
+    if (blockIdx.y == 1) {          // second sum of a launch that finishes two at once
+        part = part1;
+        G = G1;
+        nblocks = nblocks1;
+    }
     // 16 outputs per block; 16 slices of the block range per output, then a fixed-order sum.
     __shared__ float red[16][17];
     const int o = threadIdx.x & 15, sl = threadIdx.x >> 4;
@@ -679,7 +686,16 @@ hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, i
 
 hipError_t launch_outer_final(const float *part, float *G, int nb, int n_out, int accumulate, hipStream_t s)
 {
-    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 15) / 16), dim3(256), 0, s, part, G, nb, n_out, accumulate);
+    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 15) / 16), dim3(256), 0, s, part, G, nb, n_out, accumulate,
+                       (const float *)nullptr, (float *)nullptr, 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_outer_final_pair(const float *part0, float *G0, int nb0, const float *part1, float *G1, int nb1, int n_out,
+                                   int accumulate, hipStream_t s)
+{
+    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 15) / 16, 2), dim3(256), 0, s, part0, G0, nb0, n_out, accumulate, part1,
+                       G1, nb1);
     return hipGetLastError();
 }
 
@@ -693,7 +709,7 @@ int decode_outer_blocks(int R, int Cc)
 }
 
 hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const void *V, float *G, float *part, int R_all,
-                               int Cc, int r, int accumulate, int pg, hipStream_t s, RowMap rm)
+                               int Cc, int r, int accumulate, int pg, hipStream_t s, RowMap rm, bool final_sum)
 {
     if (pg <= 0) pg = R_all;
     const int R = rm.count(R_all);
@@ -707,10 +723,9 @@ hipError_t launch_decode_outer(const void *P, const void *Dm, void *Cmat, const 
     else
         hipLaunchKernelGGL((decode_mfma_kernel<false, 2, true>), dim3(nb), dim3(256), 0, s, p, d, c, R, Cc, r, chunks, v, part, pg, rm);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || !final_sum) return e;
     const int n_out = r * 16;
-    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 15) / 16), dim3(256), 0, s, part, G, nb, n_out, accumulate);
-    return hipGetLastError();
+    return launch_outer_final(part, G, nb, n_out, accumulate, s);
 }
 
 static int outer_tiles_per_block(int64_t tiles)
@@ -748,8 +763,7 @@ hipError_t launch_outer_reduce(int dtype, const void *P, const void *V, float *G
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int n_out = r * 16;
-    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 15) / 16), dim3(256), 0, s, part, G, nb, n_out, accumulate);
-    return hipGetLastError();
+    return launch_outer_final(part, G, nb, n_out, accumulate, s);
 }
 
 }  // namespace stl

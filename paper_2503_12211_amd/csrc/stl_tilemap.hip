@@ -126,30 +126,31 @@ __global__ __launch_bounds__(256) void outer_partial_kernel(const T *__restrict_
     }
 }
 
-__global__ __launch_bounds__(256) void outer_final_kernel(const float *__restrict__ part, float *__restrict__ G,
-                                                          int nblocks, int n_out, int accumulate,
-                                                          const float *__restrict__ part1 = nullptr,
-                                                          float *__restrict__ G1 = nullptr, int nblocks1 = 0)
+__global__ __launch_bounds__(1024) void outer_final_kernel(const float *__restrict__ part, float *__restrict__ G,
+                                                           int nblocks, int n_out, int accumulate,
+                                                           const float *__restrict__ part1 = nullptr,
+                                                           float *__restrict__ G1 = nullptr, int nblocks1 = 0)
 {
     if (blockIdx.y == 1) {          // second sum of a launch that finishes two at once
         part = part1;
         G = G1;
         nblocks = nblocks1;
     }
-    // 16 outputs per block; 16 slices of the block range per output, then a fixed-order sum.
-    __shared__ float red[16][17];
+    // 16 outputs per block of 1024 threads; 64 slices of the block range per output (up to 1024 partials: 16 loads per
+    // thread, all in flight together), then a fixed-order sum over the slices.
+    __shared__ float red[64][17];
     const int o = threadIdx.x & 15, sl = threadIdx.x >> 4;
     const int i = blockIdx.x * 16 + o;
     float s = 0.f;
     if (i < n_out)
-#pragma unroll 8
-        for (int b = sl; b < nblocks; b += 16) s += part[(size_t)b * n_out + i];
+#pragma unroll 16
+        for (int b = sl; b < nblocks; b += 64) s += part[(size_t)b * n_out + i];
     red[sl][o] = s;
     __syncthreads();
     if (sl == 0 && i < n_out) {
         float tot = 0.f;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) tot += red[u][o];
+        for (int u = 0; u < 64; ++u) tot += red[u][o];
         G[i] = accumulate ? G[i] + tot : tot;
     }
 }
@@ -686,7 +687,7 @@ hipError_t launch_decode(int dtype, const void *P, const void *Dm, void *Cmat, i
 
 hipError_t launch_outer_final(const float *part, float *G, int nb, int n_out, int accumulate, hipStream_t s)
 {
-    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 15) / 16), dim3(256), 0, s, part, G, nb, n_out, accumulate,
+    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 15) / 16), dim3(1024), 0, s, part, G, nb, n_out, accumulate,
                        (const float *)nullptr, (float *)nullptr, 0);
     return hipGetLastError();
 }
@@ -694,7 +695,7 @@ hipError_t launch_outer_final(const float *part, float *G, int nb, int n_out, in
 hipError_t launch_outer_final_pair(const float *part0, float *G0, int nb0, const float *part1, float *G1, int nb1, int n_out,
                                    int accumulate, hipStream_t s)
 {
-    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 15) / 16, 2), dim3(256), 0, s, part0, G0, nb0, n_out, accumulate, part1,
+    hipLaunchKernelGGL(outer_final_kernel, dim3((n_out + 15) / 16, 2), dim3(1024), 0, s, part0, G0, nb0, n_out, accumulate, part1,
                        G1, nb1);
     return hipGetLastError();
 }

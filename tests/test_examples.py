@@ -33,3 +33,37 @@ def test_class0_fit_trains_through_the_library():
     h16 = class0_fit.fit(16, steps=120, init="gauss", size=64, seed=3)
     h48 = class0_fit.fit(48, steps=120, init="gauss", size=64, seed=3)
     assert np.mean(h48[-10:]) < np.mean(h16[-10:])
+
+
+@pytest.mark.gpu
+def test_autograd_layer_matches_the_oracle_gradients():
+    """The PyTorch layer built on the C ABI: outputs and all four autograd gradients against the fp64 oracle, and a few
+    optimiser steps that lower a regression loss."""
+    import torch
+    import gpu_util as gu
+    import stl_synth
+    from oracle import planes
+    from paper_2503_12211_amd.examples.stl_linear import STLLinear, stl_linear
+    for dtype, tdt in (("bf16", torch.bfloat16), ("f32", torch.float32)):
+        p = stl_synth.stl_problem(64, 96, 128, 24, seed=41, dtype=dtype, with_dC=True)
+        X, What, E_X, D = (gu.dev(p[s], dtype).requires_grad_() for s in ("X", "What", "E_X", "D"))
+        C = stl_linear(X, What, E_X, D)
+        C.backward(gu.dev(p["dC"], dtype))
+        assert gu.rel(gu.host(C), planes.forward(p["X"], p["What"], p["E_X"], p["D"])) <= gu.TOL[dtype]
+        ref = planes.backward(p["X"], p["What"], p["E_X"], p["D"], p["dC"])
+        for t, g in zip((X, What, E_X, D), ref):
+            assert t.grad.dtype == tdt
+            assert gu.rel(gu.host(t.grad), g) <= 1.5 * gu.TOL[dtype]      # parameter gradients are rounded to the storage type
+    layer = STLLinear(64, 32, 16, dtype=torch.float32).cuda()
+    opt = torch.optim.Adam(layer.parameters(), lr=1e-2)
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    x = torch.randn((4, 32, 64), device="cuda", generator=gen)
+    target = torch.randn((4, 32, 32), device="cuda", generator=gen)
+    losses = []
+    for _ in range(30):
+        opt.zero_grad()
+        loss = ((layer(x) - target) ** 2).mean()
+        loss.backward()
+        opt.step()
+        losses.append(float(loss.detach()))
+    assert losses[-1] < 0.9 * losses[0], losses

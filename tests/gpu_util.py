@@ -94,12 +94,14 @@ def forward(p, dtype, flags=0, save_yhat=False, save_xhat=False):
     n = 4 * N
     prob = stl.Problem(m, k, n, r, STL_DT[dtype])
     X, What, E_X, D = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D"))
-    C = torch.full((m, n), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
-    Y = planes_buffer(r, m // 4, N, dtype) if save_yhat else None
-    Xh = planes_buffer(r, m // 4, k // 4, dtype) if save_xhat else None
-    ws, nbytes = workspace(prob, stl.STL_OP_FORWARD, flags)
+    gd = Guard()
+    C = gd.alloc((m, n), TORCH_DT[dtype])
+    Y = gd.alloc((stl.stl_plane_elems(m // 4, N, r),), TORCH_DT[dtype]) if save_yhat else None
+    Xh = gd.alloc((stl.stl_plane_elems(m // 4, k // 4, r),), TORCH_DT[dtype]) if save_xhat else None
+    nbytes = stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD, flags)
+    ws = gd.alloc((max(nbytes, 16),), torch.uint8, fill=None)
     stl.stl_forward(prob, X, What, E_X, D, C, Xh, Y, ws, nbytes, flags)
-    torch.cuda.synchronize()
+    gd.check()
     if save_xhat:
         return host(C), planes_to_host(Xh, r, m // 4, k // 4), planes_to_host(Y, r, m // 4, N)
     return (host(C), planes_to_host(Y, r, m // 4, N)) if save_yhat else host(C)
@@ -113,20 +115,18 @@ def backward(p, dtype, yhat=None, accumulate=0, init=None, skip=(), xhat=None):
     X, What, E_X, D, dC = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D", "dC"))
     Y = planes_to_dev(yhat, dtype) if yhat is not None else None
     Xh = planes_to_dev(xhat, dtype) if xhat is not None else None
-    dX = torch.full((m, k), float("nan"), dtype=TORCH_DT[dtype], device="cuda")
-    f32 = dict(dtype=torch.float32, device="cuda")
-    if init is None:
-        dWhat = torch.full((r, K, N), float("nan"), **f32)
-        dE_X = torch.full((r, 16), float("nan"), **f32)
-        dD = torch.full((r, 16), float("nan"), **f32)
-    else:
-        dWhat, dE_X, dD = (torch.from_numpy(np.asarray(a, dtype=np.float32)).cuda() for a in init)
-    outs = {"dX": dX, "dWhat": dWhat, "dE_X": dE_X, "dD": dD}
+    gd = Guard()
+    outs = {"dX": gd.alloc((m, k), TORCH_DT[dtype]), "dWhat": gd.alloc((r, K, N), torch.float32),
+            "dE_X": gd.alloc((r, 16), torch.float32), "dD": gd.alloc((r, 16), torch.float32)}
+    if init is not None:
+        for name, a in zip(("dWhat", "dE_X", "dD"), init):
+            outs[name].copy_(torch.from_numpy(np.asarray(a, dtype=np.float32)))
     args = {k_: (None if k_ in skip else v) for k_, v in outs.items()}
-    ws, nbytes = workspace(prob, stl.STL_OP_BACKWARD)
+    nbytes = stl.stl_workspace_bytes(prob, stl.STL_OP_BACKWARD)
+    ws = gd.alloc((max(nbytes, 16),), torch.uint8, fill=None)
     stl.stl_backward(prob, X, What, E_X, D, dC, Xh, Y, args["dX"], args["dWhat"], args["dE_X"], args["dD"],
                      accumulate, ws, nbytes)
-    torch.cuda.synchronize()
+    gd.check()
     return {k_: host(v) for k_, v in outs.items()}
 
 

@@ -261,13 +261,10 @@ static hipError_t launch_block_t(const void *Xin, const void *What, const void *
     auto kern = fused::stl_block_kernel<RP, ENCODE, GELU>;
     constexpr int smem = fused::smem_bytes<RP, ENCODE>();
     static_assert(smem <= 160 * 1024, "LDS budget");
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per instantiation (initialisation of a function-local static is thread-safe)
+    static const hipError_t attr_err =
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (attr_err != hipSuccess) return attr_err;
     const int bi = (M + fused::BI - 1) / fused::BI, bj = (N + fused::BJ - 1) / fused::BJ;
     const long total = (long)bi * bj;
     if (total > 0x7fffffffL) return hipErrorInvalidValue;

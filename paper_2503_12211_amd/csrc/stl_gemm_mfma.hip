@@ -251,13 +251,10 @@ static hipError_t launch_cfg(const GemmDesc &g, const void *A, const void *B, vo
 {
     auto kern = gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, A_T, B_T, TO, ACC>;
     constexpr int smem = 2 * (BM + BN) * BK * 2;
-    static bool attr_set = false;  // per instantiation; the attribute is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per instantiation (initialisation of a function-local static is thread-safe)
+    static const hipError_t attr_err =
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (attr_err != hipSuccess) return attr_err;
     const int tiles_m = (g.Mi + BM - 1) / BM, tiles_n = (g.Nj + BN - 1) / BN;
     const long total = (long)tiles_m * tiles_n * g.batch * g.nb;
     if (total > 0x7fffffffL) return hipErrorInvalidValue;

@@ -508,13 +508,10 @@ static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *
     constexpr int RP = (ES == 2 ? 32 : 16) / (NS == 4 ? 2 : 1) / (WN / 64);
     constexpr int smem = NS * 512 * pipe::BKS * 2 + NW * RP * (WN * ES + 16);
     static_assert(smem <= 160 * 1024, "LDS budget");
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per instantiation (initialisation of a function-local static is thread-safe)
+    static const hipError_t attr_err =
+        hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (attr_err != hipSuccess) return attr_err;
     const int tiles_m = (g.Mi + 255) / 256, tiles_n = (g.Nj + 255) / 256;
     const long total = (long)tiles_m * tiles_n * g.batch * g.nb;
     if (total > 0x7fffffffL) return hipErrorInvalidValue;

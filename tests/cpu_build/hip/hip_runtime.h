@@ -62,5 +62,5 @@ inline float __uint_as_float(uint32_t u) { float f; memcpy(&f, &u, 4); return f;
 typedef short cpu_v4i16 __attribute__((ext_vector_type(4)));
 #define __builtin_amdgcn_ds_read_tr16_b64_v4i16(p) (cpu_v4i16{0, 0, 0, 0})
 // a 16-byte global read (stands in for the LDS-DMA load): touch the bytes so that the sanitizer checks them
-inline void cpu_touch16(const void *g) { volatile uint64_t a = ((const volatile uint64_t *)g)[0], b = ((const volatile uint64_t *)g)[1]; (void)a; (void)b; }
+inline void cpu_touch16(const void *g) { if ((uintptr_t)g & 15) { fprintf(stderr, "runtime error: LDS-DMA source %p is not 16-byte aligned (%s)\n", g, g_kernel_name); abort(); } volatile uint64_t a = ((const volatile uint64_t *)g)[0], b = ((const volatile uint64_t *)g)[1]; (void)a; (void)b; }
 #define __builtin_amdgcn_sched_group_barrier(a, b, c) ((void)0)

@@ -1,7 +1,8 @@
 """Address check of the HIP kernels without a GPU.
 
 The library's sources are compiled for the host against a stand-in for the HIP runtime (tests/cpu_build/) and every
-entry point is run thread by thread under AddressSanitizer on buffers that end where their allocation ends: the real
+entry point is run thread by thread under AddressSanitizer and the alignment sanitizer on buffers that end where their
+allocation ends: the real
 index arithmetic of every kernel and of the host-side launch code is executed, and any access outside a buffer is
 reported.  (Matrix-core products and LDS contents are stubs: results are not checked here, only addresses.)
 The shapes include the full-size workloads of bench.py's extra legs and stacked / ragged backward passes at sizes the
@@ -44,7 +45,8 @@ def checker(tmp_path_factory):
         (work / f.name.replace(".hip", ".cpp")).write_text(_host_source(f.read_text()))
     shutil.copy(ROOT / "include" / "stl.h", work / "stl.h")
     shutil.copy(ROOT / "tests" / "cpu_build" / "driver.cpp", work / "driver.cpp")
-    flags = ["-x", "c++", "-std=c++17", "-O1", "-g", "-fsanitize=address", "-fno-omit-frame-pointer", "-Wno-everything",
+    flags = ["-x", "c++", "-std=c++17", "-O1", "-g", "-fsanitize=address,alignment", "-fno-sanitize-recover=alignment",
+             "-fno-omit-frame-pointer", "-Wno-everything",
              f"-I{ROOT / 'tests' / 'cpu_build'}", f"-I{work}"]
     objs, procs = [], []
     for src in sorted(work.glob("*.cpp")):
@@ -56,7 +58,7 @@ def checker(tmp_path_factory):
         out, _ = p.communicate()
         assert p.returncode == 0, f"{src.name}:\n{out[-3000:]}"
     exe = work / "address_check"
-    res = subprocess.run([str(CLANG), "-fsanitize=address", *map(str, objs), "-o", str(exe)], capture_output=True, text=True)
+    res = subprocess.run([str(CLANG), "-fsanitize=address,alignment", *map(str, objs), "-o", str(exe)], capture_output=True, text=True)
     assert res.returncode == 0, res.stderr[-3000:]
 
     def run(*cases, expect_ok=True):
@@ -64,7 +66,7 @@ def checker(tmp_path_factory):
         r = subprocess.run([str(exe), *cases], capture_output=True, text=True, env=env, timeout=900)
         text = r.stdout + r.stderr
         if expect_ok:
-            assert r.returncode == 0 and "ERROR: AddressSanitizer" not in text, text[-4000:]
+            assert r.returncode == 0 and "ERROR: AddressSanitizer" not in text and "runtime error" not in text, text[-4000:]
             assert text.count("  ok") == len(cases), text[-2000:]
         return r.returncode, text
     return run

@@ -387,7 +387,16 @@ def main():
     out["forward_variants_ms"] = variants
     log(f"  forward variants (ms): {variants}")
 
-    if not args.no_mlp:
+    # The legs below add to the one JSON line; a Python-level failure in one of them is recorded, not fatal: the headline
+    # numbers above are already measured.
+    def run_leg(name, fn):
+        try:
+            fn()
+        except Exception as e:      # noqa: BLE001
+            out.setdefault("leg_errors", {})[name] = f"{type(e).__name__}: {e}"
+            log(f"  leg {name} failed: {type(e).__name__}: {e}")
+
+    def leg_mlp():
         (mm, d_, h_, rr), calls = mlp_setup()
         pair = {name: round(T.wall(fn, max(S // 2, 2), max(W // 2, 1)), 5) for name, fn in calls.items()}
         out["mlp_pair"] = {"workload": f"C4: m={mm}, {d_} -> {h_} -> {d_}, r={rr}, GELU between the layers, bf16", "ms": pair,
@@ -395,7 +404,10 @@ def main():
         log(f"  stacked layers (ms): {pair}")
         del calls
 
-    if args.extra:
+    if not args.no_mlp:
+        run_leg("mlp", leg_mlp)
+
+    def leg_extra():
         aa_w, aa_calls = aa_setup()
         aa = {name: round(T.wall(fn, max(S // 2, 2), max(W // 2, 1)), 5) for name, fn in aa_calls.items()}
         out["two_activations"] = {"workload": aa_w, "ms": aa}
@@ -407,7 +419,10 @@ def main():
         log(f"  ragged rows (ms): {rag}")
         del rg_calls
 
-    if args.sweep:
+    if args.extra:
+        run_leg("extra", leg_extra)
+
+    def leg_sweep():
         sweep = {}
         for rr in (8, 16, 24, 32, 49, 64):
             q = stl_synth.stl_problem(8192, 4096, 4096, rr, 1003 + 100 * rr, "bf16")
@@ -451,7 +466,10 @@ def main():
             del Xq, Cq
         out["forward_square_ms"] = sq
 
-    if not args.no_cpu_baseline:
+    if args.sweep:
+        run_leg("sweep", leg_sweep)
+
+    def leg_cpu_baseline():
         import oracle
         sm = 2048                                  # bounded sample: the m=4096, k=n=2048 sub-problem, same r and distributions
         q = stl_synth.stl_problem(2 * sm, sm, sm, r, seed + 1, "bf16", with_dC=True)
@@ -470,6 +488,9 @@ def main():
             "oracle_seconds_sample": round(dt, 3),
         }
         log(f"  cpu oracle: {dt:.2f} s on {2 * sm}x{sm}x{sm} sample with {oracle.num_threads()} threads")
+
+    if not args.no_cpu_baseline:
+        run_leg("cpu", leg_cpu_baseline)
 
     print(json.dumps(out), flush=True)
 

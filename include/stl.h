@@ -200,7 +200,7 @@ stl_status_t stl_recode(const stl_problem_t *up, const stl_problem_t *down, cons
  * of B^T is the transpose of a tile of B, so B is encoded as it lies with the columns of E_B permuted accordingly, and the
  * planes are held as [p][J][L]: Bhat_save then has stl_plane_elems(nbatch*N, K, r) elements, and dB has B's shape.
  * ws / ws_bytes: at least stl_aa_workspace_bytes(prob, nbatch, STL_OP_FORWARD).
- * nbatch*m and nbatch*k may not exceed 2^24 (INVALID_ARG).
+ * nbatch*m, nbatch*k and nbatch*n may not exceed 2^24 (INVALID_ARG).  The workspace size does not depend on the flags.
  */
 size_t stl_aa_workspace_bytes(const stl_problem_t *prob, int64_t nbatch, int op);
 stl_status_t stl_aa_forward(const stl_problem_t *prob, int64_t nbatch, const void *A, const void *B,
@@ -240,6 +240,7 @@ stl_status_t stl_aa_backward(const stl_problem_t *prob, int64_t nbatch, const vo
  *   Xhat_save stl_plane_elems(nimg*Mt, K, r), Yhat_save stl_plane_elems(nimg*Mt, N, r) elements, or NULL.
  * rows >= 4 and m % rows == 0 (INVALID_ARG otherwise).
  * ws / ws_bytes: at least stl_ragged_workspace_bytes(prob, rows, STL_OP_FORWARD or STL_OP_BACKWARD).
+ * Error behaviour and ownership as for every entry point (see the top of this file); there is no activation flag here.
  */
 size_t stl_ragged_workspace_bytes(const stl_problem_t *prob, int64_t rows, int op);
 stl_status_t stl_ragged_forward(const stl_problem_t *prob, int64_t rows, const void *X, const void *What,

@@ -355,7 +355,7 @@ const char *stl_status_string(stl_status_t s)
 
 const char *stl_last_error(void) { return g_err; }
 
-const char *stl_version(void) { return "0.2.0 gfx950"; }
+const char *stl_version(void) { return "0.3.0 gfx950"; }
 
 size_t stl_plane_elems(int64_t R, int64_t Cc, int r)
 {

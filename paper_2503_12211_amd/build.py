@@ -20,14 +20,6 @@ FLAGS = [
 ]
 
 
-if os.environ.get("STL_GEMM_NS"):
-    FLAGS.append("-DSTL_GEMM_NS=" + os.environ["STL_GEMM_NS"])
-if os.environ.get("STL_GEMM_ABLATE"):       # development aid: STL_GEMM_DBG bits skip parts of the pipelined GEMM (timing only)
-    FLAGS.append("-DSTL_GEMM_ABLATE")
-if os.environ.get("STL_GEMM_TIMELINE"):     # development aid: per-block timestamps inside the pipelined GEMM
-    FLAGS.append("-DSTL_GEMM_TIMELINE")
-
-
 def sources():
     return sorted(CSRC.glob("*.hip"))
 

@@ -4,7 +4,6 @@
 #include "stl_kernels.h"
 #include "stl_device.h"
 
-#include <cstdlib>
 
 namespace stl {
 
@@ -94,8 +93,7 @@ hipError_t launch_plane_gemm_generic(int dtype, const GemmDesc &g, const void *A
 
 hipError_t launch_plane_gemm(int dtype, const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
-    static const bool use_pipe = []() { const char *e = getenv("STL_GEMM_PIPE"); return e ? atoi(e) != 0 : true; }();
-    if (dtype == 1 && use_pipe && plane_gemm_pipe_eligible(g)) return launch_plane_gemm_pipe(g, A, B, Out, s);
+    if (dtype == 1 && plane_gemm_pipe_eligible(g)) return launch_plane_gemm_pipe(g, A, B, Out, s);
     if (dtype == 1 && plane_gemm_mfma_eligible(g)) return launch_plane_gemm_mfma(g, A, B, Out, s);
     return launch_plane_gemm_generic(dtype, g, A, B, Out, s);
 }

@@ -13,7 +13,6 @@
 #include "stl_kernels.h"
 #include "stl_device.h"
 
-#include <cstdlib>
 
 namespace stl {
 
@@ -267,16 +266,10 @@ static hipError_t launch_cfg(const GemmDesc &g, const void *A, const void *B, vo
 template <bool A_T, bool B_T, typename TO, bool ACC>
 static hipError_t launch_shape(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
-    static const int forced = []() { const char *e = getenv("STL_GEMM_CFG"); return e ? atoi(e) : -1; }();
-    int cfg = forced;
-    if (cfg < 0) cfg = (g.Mi > 128 && g.Nj > 128) ? 0 : 2;
-    switch (cfg) {
-        case 0: return launch_cfg<256, 256, 2, 4, A_T, B_T, TO, ACC>(g, A, B, Out, s);   // 8 wavefronts, 128x64 each
-        case 1: return launch_cfg<256, 256, 2, 2, A_T, B_T, TO, ACC>(g, A, B, Out, s);   // 4 wavefronts, 128x128 each
-        case 3: return launch_cfg<256, 128, 2, 2, A_T, B_T, TO, ACC>(g, A, B, Out, s);   // 4 wavefronts, 128x64 each
-        case 4: return launch_cfg<128, 256, 2, 2, A_T, B_T, TO, ACC>(g, A, B, Out, s);   // 4 wavefronts, 64x128 each
-        default: return launch_cfg<128, 128, 2, 2, A_T, B_T, TO, ACC>(g, A, B, Out, s);  // 4 wavefronts, 64x64 each
-    }
+    // large planes: 256 x 256 blocks, 8 wavefronts of 128 x 64; small ones: 128 x 128 blocks, 4 wavefronts of 64 x 64
+    // (256x256 with 4 wavefronts of 128x128, 256x128 and 128x256 were measured and are not faster at any shape)
+    if (g.Mi > 128 && g.Nj > 128) return launch_cfg<256, 256, 2, 4, A_T, B_T, TO, ACC>(g, A, B, Out, s);
+    return launch_cfg<128, 128, 2, 2, A_T, B_T, TO, ACC>(g, A, B, Out, s);
 }
 
 hipError_t launch_plane_gemm_mfma(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)

@@ -14,7 +14,6 @@
 #include "stl_kernels.h"
 #include "stl_device.h"
 
-#include <cstdlib>
 #include <type_traits>
 
 namespace stl {
@@ -214,16 +213,6 @@ __device__ __forceinline__ void wait_vmcnt()
     else static_assert(N == 0, "unsupported vmcnt");
 }
 
-#ifdef STL_GEMM_TIMELINE
-__device__ unsigned long long g_timeline[8192 * 4];
-#define STL_TSTAMP(slot)                                                                   \
-    do {                                                                                   \
-        if (threadIdx.x == 0 && v < 8192) g_timeline[v * 4 + (slot)] = __builtin_amdgcn_s_memtime(); \
-    } while (0)
-#else
-#define STL_TSTAMP(slot) do { } while (0)
-#endif
-
 }  // namespace pipe
 
 // A_T: A stored [l][i];  B_T: B stored [l][j].  Requires Kl % 32 == 0, Mi % 8 == 0, Nj % 8 == 0.
@@ -237,16 +226,8 @@ __device__ unsigned long long g_timeline[8192 * 4];
 template <int WAVES_M, int WAVES_N, int NS, int SWZ, bool A_T, bool B_T, typename TO, bool ACC>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ B,
                                                         TO *__restrict__ Out, int Mi, int Nj, int Kl, int tiles_m,
-                                                        int tiles_n, int total, int dbg_arg, int a_pg, int b_pg, int o_pg, int batch)
+                                                        int tiles_n, int total, int a_pg, int b_pg, int o_pg, int batch)
 {
-    // Timing-only ablation switches (they skip parts of the kernel and give wrong results): compiled in only with
-    // -DSTL_GEMM_ABLATE; in the normal build dbg is the constant 0 and every test below folds away.
-#ifdef STL_GEMM_ABLATE
-    const int dbg = dbg_arg;
-#else
-    constexpr int dbg = 0;
-    (void)dbg_arg;
-#endif
     using namespace pipe;
     constexpr int BM = 256, BN = 256, NW = WAVES_M * WAVES_N, WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int FM = WM / 32, FN = WN / 32;
@@ -318,11 +299,9 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
         // Stage s+NS-1 is issued in iteration s; stage s+1 must have landed at the top of iteration s (fragments
         // are fetched one k16-step ahead, across the stage boundary).  Stores of the previous epilogue may still
         // be in flight: "at most N operations outstanding" then over-waits but never under-waits.
-        STL_TSTAMP(0);
         if (nks > NS - 2) wait_vmcnt<DMA_PER_STAGE * (NS - 2)>();
         else wait_vmcnt<0>();
         block_barrier();
-        STL_TSTAMP(1);
 
         bf16x8_t va[2][FM], vb[2][FN];      // fragment double buffer: [k16-step parity]
 #pragma unroll
@@ -334,12 +313,11 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
         // switch, so that the loop over the stages that refill carries no test around the DMA instructions.
         auto stage = [&](int s, auto refill_c) {
             constexpr bool REFILL = decltype(refill_c)::value;
-            if (s + 1 < nks && !(dbg & 8)) {
+            if (s + 1 < nks) {
                 if (REFILL || s + NS - 2 < nks) wait_vmcnt<DMA_PER_STAGE * (NS - 3)>();
                 else wait_vmcnt<0>();
             }
-            if (!(dbg & 4)) block_barrier();   // stage s+1 visible to all; nobody reads stage s-1 any more
-            const bool refill = REFILL && !(dbg & 16);
+            block_barrier();   // stage s+1 visible to all; nobody reads stage s-1 any more
             const uint32_t dst = smem_lds + ((s + NS - 1) % NS) * STAGE_BYTES;
             const char *cur = smem + (s % NS) * STAGE_BYTES;
             const char *nxt = smem + ((s + 1) % NS) * STAGE_BYTES;
@@ -358,7 +336,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
                     // one fragment fetch per MFMA slot, in the order the next step consumes them: B0, A0, B1, A1, ...
                     // (eight wavefronts fetching all their fragments at once fill the LDS queue, and a wavefront
                     //  stuck issuing an LDS read cannot issue the independent MFMAs behind it)
-                    if constexpr (i < FM + FN) if (!(dbg & 32)) {
+                    if constexpr (i < FM + FN) {
                         constexpr int pairs = FM < FN ? FM : FN;
                         if constexpr (i < 2 * pairs) {
                             if constexpr ((i % 2) == 0) vb[par ^ 1][i / 2] = fb.read(src + OPER_BYTES, i / 2, ks);
@@ -372,12 +350,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
                     }
                     if constexpr (REFILL && i >= 2 && (i % 2) == 0) {
                         constexpr int j = (i - 2) / 2;       // DMA slot inside this step
-                        if (refill) {
-                            if constexpr (a_side) {
-                                if constexpr (j < decltype(sa)::NI) sa.issue_one(dst, wave, j);
-                            } else {
-                                if constexpr (j < decltype(sb)::NI) sb.issue_one(dst + OPER_BYTES, wave, j);
-                            }
+                        if constexpr (a_side) {
+                            if constexpr (j < decltype(sa)::NI) sa.issue_one(dst, wave, j);
+                        } else {
+                            if constexpr (j < decltype(sb)::NI) sb.issue_one(dst + OPER_BYTES, wave, j);
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -388,10 +364,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
             step(std::integral_constant<int, 0>{}, cur, 1, std::true_type{});
             step(std::integral_constant<int, 1>{}, nxt, 0, std::false_type{});
             if constexpr (REFILL) {
-                if (refill) {
-                    sa.next_stage();
-                    sb.next_stage();
-                }
+                sa.next_stage();
+                sb.next_stage();
             }
         };
         const int n_refill = nks > NS - 1 ? nks - (NS - 1) : 0;
@@ -400,7 +374,6 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
 
         // every wavefront is done with the ring: refill it for the next block before storing this one
         block_barrier();
-        STL_TSTAMP(2);
         if (v + (int)gridDim.x < total) start_block(v + gridDim.x);
 
         // Epilogue.  With operands passed as (B fragment, A fragment) accumulator e of fragment (a, b) is
@@ -410,7 +383,6 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
         const int frow = lane & 31, fhalf = lane >> 5;
         constexpr int LPR = WN * ES / 16;                   // lanes per row in the store phase
         constexpr int RPI = 64 / LPR;                       // rows per store instruction
-        if (!(dbg & 2))
         static_for<0, FM>([&](auto a_c) {
             constexpr int a = decltype(a_c)::value;
             static_for<0, 32 / RP>([&](auto pass_c) {
@@ -443,7 +415,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
                     const int rr = it * RPI + lane / LPR;
                     const int gi = gi_base + rr;
                     const u32x4_t w = *reinterpret_cast<const u32x4_t *>(slab + rr * PITCH + (lane % LPR) * 16);
-                    if (gi < Mi && gj < Nj && !(dbg & 1)) {
+                    if (gi < Mi && gj < Nj) {
                         TO *o = outp + row_off + (size_t)rr * Nj + gj;
                         if (ACC) {
                             const f32x4_t old = *reinterpret_cast<const f32x4_t *>(o);
@@ -458,16 +430,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
                 asm volatile("" ::: "memory");
             });
         });
-        STL_TSTAMP(3);
     }
 }
-
-#ifdef STL_GEMM_TIMELINE
-extern "C" int stl_debug_timeline(unsigned long long *host_out, int n)
-{
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(pipe::g_timeline), sizeof(unsigned long long) * n);
-}
-#endif
 
 bool plane_gemm_pipe_eligible(const GemmDesc &g)
 {
@@ -499,10 +463,7 @@ static int cu_count()
 template <int WAVES_M, int WAVES_N, bool A_T, bool B_T, typename TO, bool ACC>
 static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
-#ifndef STL_GEMM_NS
-#define STL_GEMM_NS 4
-#endif
-    constexpr int NS = STL_GEMM_NS, SWZ = 2, NW = WAVES_M * WAVES_N, WN = 256 / WAVES_N;
+    constexpr int NS = 4, SWZ = 2, NW = WAVES_M * WAVES_N, WN = 256 / WAVES_N;
     auto kern = gemm_pipe_kernel<WAVES_M, WAVES_N, NS, SWZ, A_T, B_T, TO, ACC>;
     constexpr int ES = sizeof(TO);
     constexpr int RP = (ES == 2 ? 32 : 16) / (NS == 4 ? 2 : 1) / (WN / 64);
@@ -515,39 +476,40 @@ static hipError_t launch_pipe_cfg(const GemmDesc &g, const void *A, const void *
     const int tiles_m = (g.Mi + 255) / 256, tiles_n = (g.Nj + 255) / 256;
     const long total = (long)tiles_m * tiles_n * g.batch * g.nb;
     if (total > 0x7fffffffL) return hipErrorInvalidValue;
-    // one workgroup per CU that walks the block list (STL_GEMM_PERSIST=0: one block per workgroup)
-    static const bool persist = []() { const char *e = getenv("STL_GEMM_PERSIST"); return !e || atoi(e) != 0; }();
+    // one workgroup per CU that walks the block list
     const int cus = cu_count();
-    const unsigned grid = (unsigned)((persist && total > cus) ? cus : total);
-#ifdef STL_GEMM_ABLATE
-    static const int dbg = []() { const char *e = getenv("STL_GEMM_DBG"); return e ? atoi(e) : 0; }();
-#else
-    const int dbg = 0;
-#endif
+    const unsigned grid = (unsigned)(total > cus ? cus : total);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), smem, s, (const bf16_t *)A, (const bf16_t *)B, (TO *)Out, g.Mi, g.Nj,
-                       g.Kl, tiles_m, tiles_n, (int)total, dbg, g.a_rows_per_group(), g.b_rows_per_group(), g.o_rows_per_group(), g.batch);
+                       g.Kl, tiles_m, tiles_n, (int)total, g.a_rows_per_group(), g.b_rows_per_group(), g.o_rows_per_group(), g.batch);
     return hipGetLastError();
 }
 
-template <int WAVES_M, int WAVES_N>
+// The [l][row] form of an operand is chosen per operand; the fp32 (weight-gradient) output exists for the
+// doubly contraction-major form only, which is the only one the library asks for.
 static hipError_t launch_pipe_form(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
+    // eight wavefronts of 128 x 64 (four of 128 x 128 would read a third less from LDS per MFMA, but a single wavefront
+    // per SIMD cannot cover its own LDS latency: measured slower)
     if (g.out_f32) {
-        return g.accumulate ? launch_pipe_cfg<WAVES_M, WAVES_N, true, true, float, true>(g, A, B, Out, s)
-                            : launch_pipe_cfg<WAVES_M, WAVES_N, true, true, float, false>(g, A, B, Out, s);
+        if (!(g.a_kmajor && g.b_kmajor)) return hipErrorInvalidValue;
+        return g.accumulate ? launch_pipe_cfg<2, 4, true, true, float, true>(g, A, B, Out, s)
+                            : launch_pipe_cfg<2, 4, true, true, float, false>(g, A, B, Out, s);
     }
-    if (g.a_kmajor) return launch_pipe_cfg<WAVES_M, WAVES_N, true, true, bf16_t, false>(g, A, B, Out, s);
-    if (g.b_kmajor) return launch_pipe_cfg<WAVES_M, WAVES_N, false, true, bf16_t, false>(g, A, B, Out, s);
-    return launch_pipe_cfg<WAVES_M, WAVES_N, false, false, bf16_t, false>(g, A, B, Out, s);
+    if (g.accumulate) return hipErrorInvalidValue;
+    if (g.a_kmajor) {
+        if (!g.b_kmajor) return hipErrorInvalidValue;
+        return launch_pipe_cfg<2, 4, true, true, bf16_t, false>(g, A, B, Out, s);
+    }
+    if (g.b_kmajor) return launch_pipe_cfg<2, 4, false, true, bf16_t, false>(g, A, B, Out, s);
+    return launch_pipe_cfg<2, 4, false, false, bf16_t, false>(g, A, B, Out, s);
 }
 
 hipError_t launch_plane_gemm_pipe(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
-    // eight wavefronts of 128 x 64, or four of 128 x 128 (a third less LDS fragment traffic per MFMA, but a single
-    // wavefront per SIMD has to keep its own MFMA pipe full)
-    static const int waves = []() { const char *e = getenv("STL_GEMM_WAVES"); return e ? atoi(e) : 8; }();
-    if (waves == 4) return launch_pipe_form<2, 2>(g, A, B, Out, s);
-    return launch_pipe_form<2, 4>(g, A, B, Out, s);
+    // refuse here as well what plane_gemm_pipe_eligible excludes, so that a change of the dispatch rule cannot reach a
+    // form of the kernel that no test covers (stacked problems with more than one contraction stage among them)
+    if (!plane_gemm_pipe_eligible(g)) return hipErrorInvalidValue;
+    return launch_pipe_form(g, A, B, Out, s);
 }
 
 }  // namespace stl

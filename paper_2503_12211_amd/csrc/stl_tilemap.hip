@@ -4,7 +4,6 @@
 #include "stl_kernels.h"
 #include "stl_device.h"
 
-#include <cstdlib>
 
 namespace stl {
 
@@ -629,8 +628,7 @@ hipError_t launch_encode(int dtype, const void *A, const void *E, void *P, int R
     if (pg <= 0) pg = R;
     const int Rs = rm.count(R);                             // tile rows this launch walks over
     if (Rs <= 0) return hipSuccess;
-    static const bool lines = []() { const char *e = getenv("STL_ENCODE_LINES"); return e ? atoi(e) != 0 : true; }();
-    if (dtype == 1 && (Cc % 8) == 0 && !basis_f32 && lines) return launch_encode_lines(A, E, P, R, Cc, r, pg, s, rm);
+    if (dtype == 1 && (Cc % 8) == 0 && !basis_f32) return launch_encode_lines(A, E, P, R, Cc, r, pg, s, rm);
     if (dtype == 1 && (Cc % 4) == 0 && !basis_f32) {
         const int chunks = (Cc + 127) / 128;
         const long items = (long)Rs * chunks;

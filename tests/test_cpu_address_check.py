@@ -26,11 +26,15 @@ DMA = ('asm volatile("s_mov_b32 m0, %1\\n\\tglobal_load_lds_dwordx4 %0, off" ::"
 
 
 def _host_source(text: str) -> str:
-    """The few GPU-only constructs of a kernel file in host form: dynamic LDS becomes a static array, the LDS-DMA load a
-    16-byte read the sanitizer can see, hardware waits and barriers nothing."""
-    text = text.replace("extern __shared__ __align__(16) char smem[];", "static __align__(16) char smem[163840];")
+    """The few GPU-only constructs of a kernel file in host form: dynamic LDS becomes a heap block of exactly the size the launch asked for, the LDS-DMA load a
+    16-byte read the sanitizer can see whose LDS destination is checked against the dynamic LDS size of the launch, hardware
+    waits and barriers nothing."""
+    text = text.replace("extern __shared__ __align__(16) char smem[];", "char *smem = cpu_dyn_lds_ptr();")
     assert "global_load_lds" not in text or DMA in text, "LDS-DMA statement changed: update the host form"
-    text = text.replace(DMA, "cpu_touch16(g); (void)l;")
+    text = text.replace(DMA, "cpu_touch16(g, l);")
+    # LDS addresses count from the start of the dynamic array in the host form
+    for macro in ("STL_LDS", "STL_LDS_PTR"):
+        text = text.replace(f"(uint32_t)(uintptr_t){macro}(smem)", "0u")
     text = re.sub(r'asm volatile\("s_barrier" ::: "memory"\);', ";", text)
     text = re.sub(r'asm volatile\("s_waitcnt [^;]*;', ";", text)
     left = [ln for ln in text.splitlines() if "asm volatile" in ln and 'asm volatile("" :::' not in ln]

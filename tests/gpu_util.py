@@ -15,6 +15,60 @@ def rel(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
+# Per-entry bar, as a multiple of rms(O).  With bf16 storage an output passes through three roundings to bf16 (encoded
+# operand, encoded product, output); one rounding of a value with a log-uniform significand has relative rms
+# eps = 2^-8 / sqrt(3) * 0.736 = 1.66e-3, the first two reach the output through the decode sum, whose terms are
+# independent, so each contributes eps * rms(O) and the three together sqrt(3) * eps = 2.9e-3 (the measured relative
+# Frobenius error).  An entry's error is a sum of many independent terms, so it is close to normal; among 1e8 entries
+# the largest |z| stays below 6.5, and an entry whose planes happen to be large has up to 2.5 times the average
+# deviation: c = 6.5 * 2.5 * 2.9e-3 = 0.047 -> 0.05.  One wrong entry (error ~ rms(O)) is twenty times over it.
+# fp32 storage: the same with 2^-24 in place of 2^-8 and fp32 accumulation over the contraction, 5e-5.
+ENTRY_C = {"f32": 5e-5, "bf16": 5e-2}
+
+
+def _block_sums(a2, bh, bw):
+    """Sums of a 2-D array over bh x bw blocks (ragged last blocks included)."""
+    r_idx = np.arange(0, a2.shape[0], bh)
+    c_idx = np.arange(0, a2.shape[1], bw)
+    return np.add.reduceat(np.add.reduceat(a2, r_idx, axis=0), c_idx, axis=1)
+
+
+def check(G, O, dtype, name, block=256, slab=4):
+    """Full comparison of a GPU result with the oracle's: (1) relative Frobenius error of the whole tensor within
+    TOL[dtype]; (2) every entry within ENTRY_C[dtype] * rms(O); (3) the relative Frobenius error of every
+    block x block sub-matrix and of every slab of `slab` rows (a tile row for matrices) within TOL[dtype] as well, so
+    that a wrong tile row, block edge or plane cannot hide in the headroom of one norm.  Tensors with three
+    dimensions are taken plane by plane.  Returns the measured figures."""
+    G = np.asarray(G, dtype=np.float64)
+    O = np.asarray(O, dtype=np.float64)
+    assert G.shape == O.shape, (name, G.shape, O.shape)
+    assert np.isfinite(G).all(), f"{name}: non-finite entries"
+    diff = G - O
+    e2, o2 = diff * diff, O * O
+    tol = TOL[dtype]
+    whole = float(np.sqrt(e2.sum() / max(o2.sum(), 1e-300)))
+    rms = float(np.sqrt(o2.mean()))
+    worst = float(np.abs(diff).max() / max(rms, 1e-300))
+    out = {"rel": whole, "max_entry_over_rms": worst}
+    assert whole <= tol, f"{name}: relative Frobenius error {whole:.3e} > {tol}"
+    assert worst <= ENTRY_C[dtype], f"{name}: an entry is off by {worst:.3e} x rms(O) > {ENTRY_C[dtype]}"
+    if G.ndim >= 2 and G.shape[-1] >= 64 and G.shape[-2] >= 64:
+        e3 = e2.reshape(-1, G.shape[-2], G.shape[-1])
+        o3 = o2.reshape(-1, G.shape[-2], G.shape[-1])
+        wb, ws = 0.0, 0.0
+        for pl in range(e3.shape[0]):
+            be, bo = _block_sums(e3[pl], block, block), _block_sums(o3[pl], block, block)
+            wb = max(wb, float(np.sqrt((be / np.maximum(bo, 1e-300)).max())))
+            se = np.add.reduceat(e3[pl].sum(axis=1), np.arange(0, e3.shape[1], slab))
+            so = np.add.reduceat(o3[pl].sum(axis=1), np.arange(0, o3.shape[1], slab))
+            ws = max(ws, float(np.sqrt((se / np.maximum(so, 1e-300)).max())))
+        out["worst_block_rel"], out["worst_slab_rel"] = wb, ws
+        assert wb <= tol, f"{name}: a {block}x{block} block has relative error {wb:.3e} > {tol}"
+        assert ws <= tol, f"{name}: a slab of {slab} rows has relative error {ws:.3e} > {tol}"
+    print(f"    parity {name}: " + "  ".join(f"{k_}={v:.3e}" for k_, v in out.items()), flush=True)
+    return out
+
+
 def dev(a, dtype):
     """float32 numpy values (already representable in dtype) -> device tensor of that dtype."""
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda").to(TORCH_DT[dtype]).contiguous()
@@ -128,6 +182,32 @@ def backward(p, dtype, yhat=None, accumulate=0, init=None, skip=(), xhat=None):
                      accumulate, ws, nbytes)
     gd.check()
     return {k_: host(v) for k_, v in outs.items()}
+
+
+def step(p, dtype, flags=0):
+    """One training step exactly as bench.py runs it: stl_forward writing Xhat_save and Yhat_save, then stl_backward
+    reading those same device buffers.  Returns C, Xhat, Yhat (plane-major) and the four gradients as float64 numpy."""
+    m, k = p["X"].shape
+    r, K, N = p["What"].shape
+    n, M = 4 * N, m // 4
+    prob = stl.Problem(m, k, n, r, STL_DT[dtype])
+    X, What, E_X, D, dC = (dev(p[s], dtype) for s in ("X", "What", "E_X", "D", "dC"))
+    gd = Guard()
+    C = gd.alloc((m, n), TORCH_DT[dtype])
+    Xh = gd.alloc((stl.stl_plane_elems(M, K, r),), TORCH_DT[dtype])
+    Y = gd.alloc((stl.stl_plane_elems(M, N, r),), TORCH_DT[dtype])
+    outs = {"dX": gd.alloc((m, k), TORCH_DT[dtype]), "dWhat": gd.alloc((r, K, N), torch.float32),
+            "dE_X": gd.alloc((r, 16), torch.float32), "dD": gd.alloc((r, 16), torch.float32)}
+    nf = stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD, flags)
+    nb = stl.stl_workspace_bytes(prob, stl.STL_OP_BACKWARD)
+    ws_f = gd.alloc((max(nf, 16),), torch.uint8, fill=None)
+    ws_b = gd.alloc((max(nb, 16),), torch.uint8, fill=None)
+    stl.stl_forward(prob, X, What, E_X, D, C, Xh, Y, ws_f, nf, flags)
+    stl.stl_backward(prob, X, What, E_X, D, dC, Xh, Y, outs["dX"], outs["dWhat"], outs["dE_X"], outs["dD"], 0, ws_b, nb)
+    gd.check()
+    res = {k_: host(v) for k_, v in outs.items()}
+    res.update(C=host(C), Xhat=planes_to_host(Xh, r, M, K), Yhat=planes_to_host(Y, r, M, N))
+    return res
 
 
 def mlp_forward(p1, p2, dtype, flags=0):

@@ -113,9 +113,48 @@ def test_backward_matrix_core_shapes_bf16(gu, shape):
 
 
 def test_config5_full_size(gu):
-    """bf16, m=8192, k=n=4096, r=32, forward + backward at full size against the plane oracle."""
+    """bf16, m=8192, k=n=4096, r=32, backward at full size with nothing saved (Xhat and Yhat recomputed inside
+    stl_backward) against the plane oracle: whole-tensor norm, every entry, every 256 x 256 block and tile row."""
     cfg, p = stl_synth.config_problem("C5", with_dC=True)
     got = gu.backward(p, "bf16")
     ref = oracle_grads(p, use_planes=True)
     for name in NAMES:
-        assert gu.rel(got[name], ref[name]) <= gu.TOL["bf16"], name
+        gu.check(got[name], ref[name], "bf16", f"C5 recompute {name}")
+
+
+def test_config5_step_as_benchmarked(gu):
+    """The step bench.py times, at its size (bf16, m=8192, k=n=4096, r=32): stl_forward handing Xhat and Yhat to
+    stl_backward through Xhat_save / Yhat_save.  Everything the step produces -- C, the two saved plane tensors and
+    the four gradients -- against the plane oracle: whole-tensor norm, every entry, every 256 x 256 block and every
+    tile row (see gpu_util.check)."""
+    cfg, p = stl_synth.config_problem("C5", with_dC=True)
+    got = gu.step(p, "bf16")
+    Cref, Yref = planes.forward(p["X"], p["What"], p["E_X"], p["D"], return_yhat=True)
+    gu.check(got["C"], Cref, "bf16", "C5 step C")
+    gu.check(got["Yhat"], Yref, "bf16", "C5 step Yhat", slab=1)
+    del Cref, Yref
+    gu.check(got["Xhat"], planes.encode(p["X"], p["E_X"]), "bf16", "C5 step Xhat", slab=1)
+    ref = oracle_grads(p, use_planes=True)
+    for name in NAMES:
+        gu.check(got[name], ref[name], "bf16", f"C5 step {name}")
+    # sampled 8x8-tile blocks of C against the literal per-tile definition as well
+    rng = np.random.default_rng(5)
+    for _ in range(3):
+        I0, J0 = int(rng.integers(0, 2048 - 8)), int(rng.integers(0, 1024 - 8))
+        blk = oracle.forward_block(p["X"], p["What"], p["E_X"], p["D"], I0, I0 + 8, J0, J0 + 8)
+        assert gu.rel(got["C"][4 * I0:4 * I0 + 32, 4 * J0:4 * J0 + 32], blk) <= 2 * gu.TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_step_mid_size_every_entry(gu, dtype):
+    """The same saved-plane step at a size that spans several blocks with ragged edges (M = 328, K = 136, N = 200 tile
+    counts), both storage types, every output with the full set of checks."""
+    p = stl_synth.stl_problem(1312, 544, 800, 24, seed=91, dtype=dtype, with_dC=True)
+    got = gu.step(p, dtype)
+    Cref, Yref = planes.forward(p["X"], p["What"], p["E_X"], p["D"], return_yhat=True)
+    gu.check(got["C"], Cref, dtype, "C")
+    gu.check(got["Yhat"], Yref, dtype, "Yhat", slab=1)
+    gu.check(got["Xhat"], planes.encode(p["X"], p["E_X"]), dtype, "Xhat", slab=1)
+    ref = oracle_grads(p, use_planes=True)
+    for name in NAMES:
+        gu.check(got[name], ref[name], dtype, name)

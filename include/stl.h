@@ -124,6 +124,26 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
                          void *ws, size_t ws_bytes, int flags, void *stream);
 
 /*
+ * stl_forward for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operator, same kernels and same results as
+ * stl_forward(..., Xhat_save = NULL, Yhat_save = NULL, flags = STL_FLAG_UNFUSED | (flags & STL_FLAG_GELU)) taken in
+ * one slab, but the two plane tensors (Xhat, Yhat) live in a scratch array built into the library's device code
+ * (STL_STATIC_SCRATCH_BYTES per GPU, held from the library's first use on that GPU until the process ends) instead
+ * of a caller workspace.  The call itself allocates and frees nothing.
+ * X, What, E_X, D (in), C (out): as for stl_forward.  flags: 0 or STL_FLAG_GELU (anything else: STL_ERR_UNSUPPORTED).
+ * Limit: stl_workspace_bytes(prob, STL_OP_FORWARD, STL_FLAG_UNFUSED) must not exceed STL_STATIC_SCRATCH_BYTES, i.e.
+ *   r * roundup(M, 64) * (K + N) * sizeof(element), each tensor rounded up to 256 bytes; larger problems are rejected
+ *   with STL_ERR_WORKSPACE before anything is launched.
+ * The first call on a device looks up that device's copy of the array (hipGetSymbolAddress); make that call outside
+ * a graph capture.  All calls on one GPU share the one array, which keeps the previous call's contents (every element
+ * a call reads it has written before): calls that overlap in time on one GPU -- on different streams or from different
+ * threads -- race; calls on one stream are ordered by the stream.
+ */
+#define STL_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+stl_status_t stl_forward_static(const stl_problem_t *prob, const void *X, const void *What,
+                                const void *E_X, const void *D, void *C, int flags, void *stream);
+
+/*
  * Backward of the scalar <dC, C> (chain rule through Algorithm 1's three linear steps;
  * the paper states only that these gradients exist, Section "Strassen-Tile Operator"):
  *   dYhat[p][I][J] = sum_q D[p][q] dc[I][J][q]          dD[p][q]   = sum_{I,J} Yhat[p][I][J] dc[I][J][q]

@@ -21,7 +21,7 @@ STL_FLAG_B_TRANSPOSED = 0x200
 
 # every symbol include/stl.h declares
 SYMBOLS = (
-    "stl_plane_elems", "stl_workspace_bytes", "stl_encode_weight", "stl_encode_weight_backward", "stl_forward", "stl_backward", "stl_encode_activation",
+    "stl_plane_elems", "stl_workspace_bytes", "stl_encode_weight", "stl_encode_weight_backward", "stl_forward", "stl_forward_static", "stl_backward", "stl_encode_activation",
     "stl_plane_matmul", "stl_decode", "stl_mlp_workspace_bytes", "stl_mlp_forward", "stl_recode",
     "stl_aa_workspace_bytes", "stl_aa_forward", "stl_aa_backward",
     "stl_ragged_workspace_bytes", "stl_ragged_forward", "stl_ragged_backward",
@@ -77,6 +77,8 @@ def _load():
     lib.stl_encode_weight.argtypes = [pp, _P, _P, _P, _P]
     lib.stl_encode_weight_backward.argtypes = [pp, _P, _P, _P, _P, _P, ctypes.c_int, _P, ctypes.c_size_t, _P]
     lib.stl_forward.argtypes = [pp, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, ctypes.c_int, _P]
+    lib.stl_forward_static.argtypes = [pp, _P, _P, _P, _P, _P, ctypes.c_int, _P]
+    lib.stl_forward_static.restype = ctypes.c_int
     lib.stl_backward.argtypes = [pp, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_int, _P, ctypes.c_size_t, _P]
     lib.stl_encode_activation.argtypes = [pp, _P, _P, _P, _P]
     lib.stl_plane_matmul.argtypes = [pp, _P, _P, _P, _P]
@@ -169,6 +171,14 @@ def stl_forward(prob: Problem, X, What, E_X, D, C, Xhat_save=None, Yhat_save=Non
                 flags: int = STL_FLAG_AUTO, stream=None) -> None:
     _check(_load().stl_forward(ctypes.byref(prob.c()), _ptr(X), _ptr(What), _ptr(E_X), _ptr(D), _ptr(C),
                                _ptr(Xhat_save), _ptr(Yhat_save), _ptr(ws), ws_bytes, flags, _stream(stream)))
+
+
+STL_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def stl_forward_static(prob: Problem, X, What, E_X, D, C, flags: int = 0, stream=None) -> None:
+    _check(_load().stl_forward_static(ctypes.byref(prob.c()), _ptr(X), _ptr(What), _ptr(E_X), _ptr(D), _ptr(C), flags,
+                                      _stream(stream)))
 
 
 def stl_backward(prob: Problem, X, What, E_X, D, dC, Xhat_saved, Yhat_saved, dX, dWhat, dE_X, dD,

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 namespace {
 
@@ -337,6 +338,62 @@ RagWs ragged_layout(const Ragged &g, bool backward)
         if (e__ != hipSuccess) return hip_fail(e__, what); \
     } while (0)
 
+
+// Algorithm 1 as three launches over caller-visible plane buffers.  Output rows are independent, so when neither plane
+// tensor is handed back (`slabs`) the rows can be taken in slabs that reuse the same plane scratch: the planes of a slab
+// are then still in the 256 MB last-level cache when the next kernel reads them, instead of having been pushed out by
+// the rest of a large problem.  A slab holds about 128 MB of planes, in multiples of the plane products' 256-row
+// blocks, and at least 1024 tile rows.
+stl_status_t forward_three_launch(const stl_problem_t *prob, const Dims &d, const void *X, const void *What, const void *E_X,
+                                  const void *D, void *C, void *xhat, void *yhat, bool slabs, bool gelu, hipStream_t s)
+{
+    int slab_rows = d.M;
+    const size_t row_bytes = (size_t)d.r * ((size_t)d.K + d.N) * d.es;      // Xhat + Yhat bytes per tile row
+    if (slabs && row_bytes * d.M > ((size_t)192 << 20)) {
+        const size_t fit = ((size_t)128 << 20) / row_bytes;                 // tile rows whose planes take 128 MB
+        // shorter slabs than 1024 tile rows cost the plane products more than the cache gives back (measured)
+        if (fit >= 1024 && (int)(fit / 256) * 256 < d.M) slab_rows = (int)(fit / 256) * 256;
+    }
+    for (int r0 = 0; r0 < d.M; r0 += slab_rows) {
+        const int rows = d.M - r0 < slab_rows ? d.M - r0 : slab_rows;
+        const char *Xs = (const char *)X + (size_t)r0 * 4 * prob->k * d.es;
+        char *Cs = (char *)C + (size_t)r0 * 4 * prob->n * d.es;
+        STL_HIP(stl::launch_encode(prob->dtype, Xs, E_X, xhat, rows, d.K, d.r, PG, s), "forward/encode");
+        stl::GemmDesc g{rows, d.N, d.K, d.r, false, true, false, false, PG, 0, PG};
+        STL_HIP(stl::launch_plane_gemm(prob->dtype, g, xhat, What, yhat, s), "forward/plane products");
+        STL_HIP(stl::launch_decode(prob->dtype, yhat, D, Cs, rows, d.N, d.r, gelu, PG, s), "forward/decode");
+    }
+    return STL_OK;
+}
+
+// Built-in scratch of stl_forward_static: a device array that lives in the library's code object, so the entry point
+// needs neither a caller workspace nor any allocation.  Each GPU the library runs on holds its own copy at its own
+// address until the process ends.  In host code the array's name is only a handle for the runtime's symbol lookup,
+// never a device address: the address is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = STL_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_scratch_mu;
+char *g_scratch_ptr[kMaxDevices] = {};
+
+stl_status_t static_scratch_base(char **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "stl_forward_static/hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(STL_ERR_UNSUPPORTED, "stl_forward_static: device ordinal %d not below %d", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));       // address of THIS device's copy (the current device)
+        if (e != hipSuccess) return hip_fail(e, "stl_forward_static/hipGetSymbolAddress");
+        if (!p || ((uintptr_t)p & 255)) return fail(STL_ERR_HIP, "stl_forward_static: built-in scratch address %p is unusable", p);
+        g_scratch_ptr[dev] = (char *)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return STL_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -500,27 +557,31 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
         return STL_OK;
     }
     void *yhat = Yhat_save ? Yhat_save : (void *)(base + w.yhat);
-    // Output rows are independent, so when neither plane tensor is handed back the rows can be taken in slabs that
-    // reuse the same plane scratch: the planes of a slab are then still in the 256 MB last-level cache when the next
-    // kernel reads them, instead of having been pushed out by the rest of a large problem.  A slab holds about 128 MB
-    // of planes, in multiples of the plane products' 256-row blocks, and at least 1024 tile rows.
-    int slab_rows = d.M;
-    const size_t row_bytes = (size_t)d.r * ((size_t)d.K + d.N) * d.es;      // Xhat + Yhat bytes per tile row
-    if (!Xhat_save && !Yhat_save && row_bytes * d.M > ((size_t)192 << 20)) {
-        const size_t fit = ((size_t)128 << 20) / row_bytes;                 // tile rows whose planes take 128 MB
-        // shorter slabs than 1024 tile rows cost the plane products more than the cache gives back (measured)
-        if (fit >= 1024 && (int)(fit / 256) * 256 < d.M) slab_rows = (int)(fit / 256) * 256;
-    }
-    for (int r0 = 0; r0 < d.M; r0 += slab_rows) {
-        const int rows = d.M - r0 < slab_rows ? d.M - r0 : slab_rows;
-        const char *Xs = (const char *)X + (size_t)r0 * 4 * prob->k * d.es;
-        char *Cs = (char *)C + (size_t)r0 * 4 * prob->n * d.es;
-        STL_HIP(stl::launch_encode(prob->dtype, Xs, E_X, xhat, rows, d.K, d.r, PG, s), "forward/encode");
-        stl::GemmDesc g{rows, d.N, d.K, d.r, false, true, false, false, PG, 0, PG};
-        STL_HIP(stl::launch_plane_gemm(prob->dtype, g, xhat, What, yhat, s), "forward/plane products");
-        STL_HIP(stl::launch_decode(prob->dtype, yhat, D, Cs, rows, d.N, d.r, gelu, PG, s), "forward/decode");
-    }
-    return STL_OK;
+    return forward_three_launch(prob, d, X, What, E_X, D, C, xhat, yhat, !Xhat_save && !Yhat_save, gelu, s);
+}
+
+stl_status_t stl_forward_static(const stl_problem_t *prob, const void *X, const void *What, const void *E_X, const void *D,
+                                void *C, int flags, void *stream)
+{
+    Dims d;
+    stl_status_t st = check_problem(prob, &d);
+    if (st != STL_OK) return st;
+    if (flags & ~STL_FLAG_GELU) return fail(STL_ERR_UNSUPPORTED, "stl_forward_static: unknown flag bits 0x%x", flags);
+    if (!X || !What || !E_X || !D || !C) return fail(STL_ERR_INVALID_ARG, "stl_forward_static: NULL pointer");
+    if (any_misaligned(X, What, E_X, D, C)) return fail(STL_ERR_INVALID_ARG, "stl_forward_static: pointer not 16-byte aligned");
+    const FwdWs w = fwd_layout(d, STL_FLAG_UNFUSED);
+    if (w.total > kStaticScratchBytes)
+        return fail(STL_ERR_WORKSPACE,
+                    "stl_forward_static: the encoded planes of this problem take %zu bytes, the built-in scratch holds %zu "
+                    "(STL_STATIC_SCRATCH_BYTES); use stl_forward with a caller workspace",
+                    w.total, kStaticScratchBytes);
+    char *base = nullptr;
+    st = static_scratch_base(&base);
+    if (st != STL_OK) return st;
+    // every element of the two plane tensors that a later kernel reads is written first by an earlier kernel of this
+    // same call (encode writes Xhat, the plane products write Yhat), so nothing of the previous call has to be cleared
+    return forward_three_launch(prob, d, X, What, E_X, D, C, base + w.xhat, base + w.yhat, false,
+                                (flags & STL_FLAG_GELU) != 0, (hipStream_t)stream);
 }
 
 stl_status_t stl_backward(const stl_problem_t *prob, const void *X, const void *What, const void *E_X, const void *D,

@@ -239,3 +239,32 @@ def test_ragged_argument_checks():
     with pytest.raises(stl.StlError) as e:
         stl.stl_ragged_forward(even, 196, FAKE, FAKE, FAKE, FAKE, None, FAKE, None, None, None, 0, stream=0)
     assert e.value.status == 3
+
+
+def test_forward_static_rejects_before_any_device_call():
+    """stl_forward_static validates on the host: bad arguments, unknown flags and problems whose planes do not fit the
+    built-in scratch are refused without touching a device."""
+    small = stl.Problem(256, 256, 256, 32)
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_forward_static(small, None, FAKE, FAKE, FAKE, FAKE, 0, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_forward_static(small, FAKE, FAKE, FAKE, FAKE, FAKE + 4, 0, stream=0)
+    assert e.value.status == 1 and "aligned" in str(e.value)
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_forward_static(small, FAKE, FAKE, FAKE, FAKE, FAKE, stl.STL_FLAG_FUSED, stream=0)
+    assert e.value.status == 2
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_forward_static(stl.Problem(254, 256, 256, 32), FAKE, FAKE, FAKE, FAKE, FAKE, 0, stream=0)
+    assert e.value.status == 1
+    # largest that fits and smallest that does not: r * roundup(M, 64) * (K + N) * 2 bytes against 64 MiB
+    fits = stl.Problem(4 * 1024, 2048, 2048, 32)
+    assert stl.stl_workspace_bytes(fits, stl.STL_OP_FORWARD, stl.STL_FLAG_UNFUSED) == stl.STL_STATIC_SCRATCH_BYTES
+    over = stl.Problem(4 * 1025, 2048, 2048, 32)
+    assert stl.stl_workspace_bytes(over, stl.STL_OP_FORWARD, stl.STL_FLAG_UNFUSED) > stl.STL_STATIC_SCRATCH_BYTES
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_forward_static(over, FAKE, FAKE, FAKE, FAKE, FAKE, 0, stream=0)
+    assert e.value.status == 3 and "built-in scratch" in str(e.value)
+    header = (ROOT / "include" / "stl.h").read_text()
+    assert "#define STL_STATIC_SCRATCH_BYTES ((size_t)64 << 20)" in header
+

@@ -33,7 +33,7 @@
  *    the default stream); they never synchronise and keep no state between calls.
  *  - Every argument is validated before any launch.  Nothing is launched when a
  *    non-STL_OK status is returned for an argument error.  Supported: t == 4,
- *    1 <= r <= 64, m, k, n positive multiples of t, dtype in {F32, BF16}.
+ *    1 <= r <= 64, m, k, n positive multiples of t not above STL_MAX_DIM, dtype in {F32, BF16}.
  *  - dtype selects the storage type of X, W, What, E_X, E_W, D, C, dC, dX, Xhat,
  *    Yhat.  Arithmetic: fp32 multiply-add throughout for F32; for BF16 the plane
  *    products are bf16 x bf16 -> fp32 on MFMA, encode/decode are fp32, and each
@@ -68,6 +68,9 @@ typedef struct {
     int32_t dtype;     /* stl_dtype_t */
 } stl_problem_t;
 
+/* Largest m, k or n (and largest stacked row count of the batched entry points): 65535 * 256, so that every launch
+ * extent of every kernel, the any-shape ones included, stays within the device's grid limits. */
+#define STL_MAX_DIM 16776960
 #define STL_PLANE_GROUP 64
 /* Elements of an activation-side plane tensor with r planes of R x Cc tiles (rows rounded up to the group). */
 size_t stl_plane_elems(int64_t R, int64_t Cc, int r);
@@ -220,7 +223,7 @@ stl_status_t stl_recode(const stl_problem_t *up, const stl_problem_t *down, cons
  * of B^T is the transpose of a tile of B, so B is encoded as it lies with the columns of E_B permuted accordingly, and the
  * planes are held as [p][J][L]: Bhat_save then has stl_plane_elems(nbatch*N, K, r) elements, and dB has B's shape.
  * ws / ws_bytes: at least stl_aa_workspace_bytes(prob, nbatch, STL_OP_FORWARD).
- * nbatch*m, nbatch*k and nbatch*n may not exceed 2^24 (INVALID_ARG).  The workspace size does not depend on the flags.
+ * nbatch*m, nbatch*k and nbatch*n may not exceed STL_MAX_DIM (INVALID_ARG).  The workspace size does not depend on the flags.
  */
 size_t stl_aa_workspace_bytes(const stl_problem_t *prob, int64_t nbatch, int op);
 stl_status_t stl_aa_forward(const stl_problem_t *prob, int64_t nbatch, const void *A, const void *B,

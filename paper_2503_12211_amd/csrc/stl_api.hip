@@ -35,7 +35,7 @@ struct Dims {
 
 constexpr int PG = stl::kPlaneGroup;   // layout of Xhat, Yhat, dYhat, dXhat; What and dWhat are plane-major (0)
 
-constexpr int64_t kMaxDim = (int64_t)1 << 24;  // per-dimension cap; keeps tile indices in int
+constexpr int64_t kMaxDim = STL_MAX_DIM;  // per-dimension cap: tile indices fit an int and every grid extent the device's limits
 
 stl_status_t check_problem(const stl_problem_t *p, Dims *d)
 {

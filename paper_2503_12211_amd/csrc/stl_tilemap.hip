@@ -24,25 +24,26 @@ __global__ __launch_bounds__(256) void encode_kernel(const T *__restrict__ A, co
     __syncthreads();
 
     const int L = blockIdx.x * blockDim.x + threadIdx.x;
-    const int idx = blockIdx.y * blockDim.y + threadIdx.y;
-    if (L >= Cc || idx >= R) return;
-    const int I = rm.tile_row(idx), nv = rm.valid(I);
-    const size_t r0 = rm.row0(I);
-
+    if (L >= Cc) return;
     const size_t ld = (size_t)Cc * 4;
-    float x[16];
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) x[a * 4 + b] = a < nv ? Elem<T>::ld(A + (r0 + a) * ld + (size_t)L * 4 + b) : 0.f;
-
     const size_t plane = (size_t)pg * Cc;
-    T *out = P + plane_row_base(I, pg, r, Cc) + L;
-    for (int p = 0; p < r; ++p) {
-        float s = 0.f;
+    // grid-stride over the tile rows: the grid's second extent is capped, any row count is covered
+    for (int idx = blockIdx.y * blockDim.y + threadIdx.y; idx < R; idx += gridDim.y * blockDim.y) {
+        const int I = rm.tile_row(idx), nv = rm.valid(I);
+        const size_t r0 = rm.row0(I);
+        float x[16];
 #pragma unroll
-        for (int q = 0; q < 16; ++q) s = fmaf(sE[p * 16 + q], x[q], s);
-        Elem<T>::st(out + (size_t)p * plane, s);
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) x[a * 4 + b] = a < nv ? Elem<T>::ld(A + (r0 + a) * ld + (size_t)L * 4 + b) : 0.f;
+
+        T *out = P + plane_row_base(I, pg, r, Cc) + L;
+        for (int p = 0; p < r; ++p) {
+            float s = 0.f;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) s = fmaf(sE[p * 16 + q], x[q], s);
+            Elem<T>::st(out + (size_t)p * plane, s);
+        }
     }
 }
 
@@ -59,30 +60,31 @@ __global__ __launch_bounds__(256) void decode_kernel(const T *__restrict__ P, co
     __syncthreads();
 
     const int J = blockIdx.x * blockDim.x + threadIdx.x;
-    const int idx = blockIdx.y * blockDim.y + threadIdx.y;
-    if (J >= Cc || idx >= R) return;
-    const int I = rm.tile_row(idx), nv = rm.valid(I);
-    const size_t r0 = rm.row0(I);
-
+    if (J >= Cc) return;
     const size_t plane = (size_t)pg * Cc;
-    const T *in = P + plane_row_base(I, pg, r, Cc) + J;
-    float c[16];
-#pragma unroll
-    for (int q = 0; q < 16; ++q) c[q] = 0.f;
-    for (int p = 0; p < r; ++p) {
-        const float y = Elem<T>::ld(in + (size_t)p * plane);
-#pragma unroll
-        for (int q = 0; q < 16; ++q) c[q] = fmaf(sD[p * 16 + q], y, c[q]);
-    }
     const size_t ld = (size_t)Cc * 4;
+    // grid-stride over the tile rows, as in the encode
+    for (int idx = blockIdx.y * blockDim.y + threadIdx.y; idx < R; idx += gridDim.y * blockDim.y) {
+        const int I = rm.tile_row(idx), nv = rm.valid(I);
+        const size_t r0 = rm.row0(I);
+        const T *in = P + plane_row_base(I, pg, r, Cc) + J;
+        float c[16];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+        for (int q = 0; q < 16; ++q) c[q] = 0.f;
+        for (int p = 0; p < r; ++p) {
+            const float y = Elem<T>::ld(in + (size_t)p * plane);
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            float v = c[a * 4 + b];
-            if (GELU) v = gelu_erf(v);
-            if (a < nv) Elem<T>::st(Cmat + (r0 + a) * ld + (size_t)J * 4 + b, v);
+            for (int q = 0; q < 16; ++q) c[q] = fmaf(sD[p * 16 + q], y, c[q]);
         }
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                float v = c[a * 4 + b];
+                if (GELU) v = gelu_erf(v);
+                if (a < nv) Elem<T>::st(Cmat + (r0 + a) * ld + (size_t)J * 4 + b, v);
+            }
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -617,7 +619,7 @@ template <typename T, typename TB>
 static hipError_t launch_encode_t(const void *A, const void *E, void *P, int Rs, int Cc, int r, int pg, const RowMap &rm,
                                   hipStream_t s)
 {
-    dim3 block(64, 4), grid((Cc + 63) / 64, (Rs + 3) / 4);
+    dim3 block(64, 4), grid((Cc + 63) / 64, (Rs + 3) / 4 > 32768 ? 32768 : (Rs + 3) / 4);   // the kernel strides over the rows
     hipLaunchKernelGGL((encode_kernel<T, TB>), grid, block, 0, s, (const T *)A, (const TB *)E, (T *)P, Rs, Cc, r, pg, rm);
     return hipGetLastError();
 }
@@ -645,7 +647,7 @@ template <typename T, typename TB>
 static hipError_t launch_decode_t(const void *P, const void *Dm, void *Cmat, int Rs, int Cc, int r, bool gelu, int pg,
                                   const RowMap &rm, hipStream_t s)
 {
-    dim3 block(64, 4), grid((Cc + 63) / 64, (Rs + 3) / 4);
+    dim3 block(64, 4), grid((Cc + 63) / 64, (Rs + 3) / 4 > 32768 ? 32768 : (Rs + 3) / 4);   // the kernel strides over the rows
     if (gelu)
         hipLaunchKernelGGL((decode_kernel<T, TB, true>), grid, block, 0, s, (const T *)P, (const TB *)Dm, (T *)Cmat, Rs, Cc, r,
                            pg, rm);

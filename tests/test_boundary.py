@@ -268,3 +268,13 @@ def test_forward_static_rejects_before_any_device_call():
     header = (ROOT / "include" / "stl.h").read_text()
     assert "#define STL_STATIC_SCRATCH_BYTES ((size_t)64 << 20)" in header
 
+
+def test_dimension_cap_is_the_documented_one():
+    header = (ROOT / "include" / "stl.h").read_text()
+    cap = int(re.search(r"#define STL_MAX_DIM (\d+)", header).group(1))
+    assert cap == 65535 * 256
+    assert stl.stl_workspace_bytes(stl.Problem(cap, 4, 4, 1), stl.STL_OP_FORWARD) > 0
+    assert stl.stl_workspace_bytes(stl.Problem(cap + 4, 4, 4, 1), stl.STL_OP_FORWARD) == 0
+    with pytest.raises(stl.StlError) as e:
+        stl.stl_forward(stl.Problem(4, cap + 4, 4, 1), FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 1 << 40, 0, stream=0)
+    assert e.value.status == 1

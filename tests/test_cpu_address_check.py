@@ -88,6 +88,13 @@ def test_core_path_addresses(checker):
             "mlp:1024:256:1024:24", "mlp:64:40:36:9", "ewb:256:384:24", "ewb:64:36:8", "f32,ewb:96:160:17")
 
 
+def test_tall_matrix_stays_within_grid_limits(checker):
+    """More than a million tile rows through the any-shape kernels (fp32 storage; bf16 with a tile count that no
+    matrix-core kernel takes): every launch extent must stay within the device limits, which the stand-in runtime
+    checks for every launch, and every access in bounds."""
+    checker("f32,bwd:4200000:8:8:2", "bwd:4200000:4:12:3")
+
+
 def test_two_activation_addresses(checker):
     checker("aa:3:256:128:256:32", "aa:2:1024:640:768:16", "aa:5:72:40:56:49", "aa:2:36:20:28:7", "f32,aa:3:64:32:48:17",
             "aa:8:1024:1024:1024:32")

@@ -42,8 +42,10 @@ def seven_product_basis_4x4():
 
 
 def fit(r: int, steps: int = 300, init: str = "strassen", seed: int = 0, size: int = 128, lr: float = 3e-3,
-        log_every: int = 0):
-    """Returns the list of per-step estimates of alpha (before each update)."""
+        log_every: int = 0, trace: list | None = None, trace_steps: int = 0):
+    """Returns the list of per-step estimates of alpha (before each update).  With `trace` (a list) the first
+    `trace_steps` steps append a dict of host copies of what the step saw and produced -- X, W, the three bases before
+    the update, alpha, the upstream gradient dC and the three basis gradients -- so that a test can recompute the step independently."""
     import torch
 
     import paper_2503_12211_amd as stl
@@ -88,6 +90,10 @@ def fit(r: int, steps: int = 300, init: str = "strassen", seed: int = 0, size: i
         dC = (resid * (2.0 / (m * n * K))).contiguous()
         stl.stl_backward(prob, X, What, E_X, D, dC, Xhat, Yhat, None, dWhat, E_X.grad, D.grad, 0, ws, sizes[1])
         stl.stl_encode_weight_backward(prob, W, E_W, dWhat, None, E_W.grad, 0, ws, sizes[2])
+        if trace is not None and step < trace_steps:
+            host = lambda t_: t_.detach().cpu().numpy().astype(np.float64)
+            trace.append({"X": host(X), "W": host(W), "E_X": host(E_X), "E_W": host(E_W), "D": host(D), "alpha": alpha, "dC": host(dC),
+                          "dE_X": host(E_X.grad), "dE_W": host(E_W.grad), "dD": host(D.grad)})
         opt.step()
         if log_every and step % log_every == 0:
             print(f"  r={r} {init}: step {step:5d}  alpha {alpha:.4f}", flush=True)

@@ -36,6 +36,43 @@ def test_class0_fit_trains_through_the_library():
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("init,r", [("strassen", 32), ("gauss", 24), ("strassen", 49)])
+def test_class0_steps_against_the_oracle(init, r):
+    """The first training steps of the Class-0 fit recomputed by the oracle on the same tiles and the same bases: the
+    error estimate alpha, and the gradients of all three bases (dE_X and dD from the backward oracle, dE_W through the
+    oracle of the weight encoding), fp32 storage."""
+    import oracle
+    from oracle import planes
+    trace = []
+    class0_fit.fit(r, steps=3, init=init, size=64, seed=11, trace=trace, trace_steps=3)
+    assert len(trace) == 3
+    for i, t in enumerate(trace):
+        m, k = t["X"].shape
+        n = t["W"].shape[1]
+        What = oracle.encode_weight(t["W"], t["E_W"])
+        C = oracle.forward(t["X"], What, t["E_X"], t["D"])
+        resid = C - t["X"] @ t["W"]
+        alpha = float((resid * resid).sum() / (m * n * (k // 4)))
+        dC = resid * (2.0 / (m * n * (k // 4)))
+        if alpha > 1e-3:                                         # away from the exact basis the fp32 residual is accurate
+            assert np.linalg.norm(t["dC"] - dC) <= 1e-4 * np.linalg.norm(dC), i
+        # gradients for the upstream gradient the step actually used (near the exact basis the fp32 residual C - X W
+        # is mostly rounding of its two terms, which is the example's arithmetic, not the library's)
+        _, dWhat, dE_X, dD = oracle.backward(t["X"], What, t["E_X"], t["D"], t["dC"])
+        _, dE_W = planes.encode_weight_backward(t["W"], t["E_W"], dWhat)
+        if init == "strassen" and r == 49 and i == 0:
+            assert alpha < 1e-20 and t["alpha"] < 1e-9           # exact basis: nothing but rounding
+            continue
+        assert abs(t["alpha"] - alpha) <= 1e-4 * alpha + 1e-9, (i, t["alpha"], alpha)
+        for name, ref in (("dE_X", dE_X), ("dE_W", dE_W), ("dD", dD)):
+            err = np.linalg.norm(t[name] - ref) / np.linalg.norm(ref)
+            assert err <= 2e-5, (i, name, err)       # two chained fp32 passes (backward, then the weight encoding's)
+        if i:
+            for name in ("E_X", "E_W", "D"):                     # the optimiser moved the bases between the steps
+                assert not np.array_equal(t[name], trace[i - 1][name])
+
+
+@pytest.mark.gpu
 def test_autograd_layer_matches_the_oracle_gradients():
     """The PyTorch layer built on the C ABI: outputs and all four autograd gradients against the fp64 oracle, and a few
     optimiser steps that lower a regression loss."""

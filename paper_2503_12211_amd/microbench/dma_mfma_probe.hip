@@ -1,0 +1,139 @@
+// Probe of the two resources the pipelined plane-product kernel lives on, in that kernel's own access pattern:
+// the L2 -> LDS path (LDS-DMA loads, global_load_lds_dwordx4) and the matrix cores (32x32x16 bf16 MFMA).
+// One workgroup of eight wavefronts per CU walks over the same (plane, 256 x 256 block) list as the library's
+// kernel at the benchmark shape (r planes of M x K times K x N tiles) and per 32-element contraction stage either
+//   * only issues the loads of the stage (nobody reads the data),          mode bit 0
+//   * only issues the stage's sixteen MFMAs per wavefront on register operands, mode bit 1
+//   * or both, interleaved as in the library's kernel.
+// The first operand ([row][l]: 64 contiguous bytes per row and stage) can be fetched as the kernel does it today --
+// half a 128-byte line per row and stage -- or as whole lines (64 contraction elements per row every second stage):
+// same bytes, half the number of L2 requests for that operand.                mode bit 2 = whole lines
+// Results are timings only; this file is measurement code, not part of the library.
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include <cstdio>
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ void dma16(const uint16_t *g, uint32_t lds_wave_base)
+{
+    const uint32_t l = __builtin_amdgcn_readfirstlane(lds_wave_base);
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(l) : "memory", "m0");
+}
+
+template <int MODE>
+__global__ __launch_bounds__(512) void probe_kernel(const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int Mi,
+                                                    int Nj, int Kl, int planes, float *__restrict__ sink)
+{
+    constexpr bool DMA = MODE & 1, MFMA = MODE & 2, WIDE = MODE & 4;
+    extern __shared__ __align__(16) char smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tiles_m = Mi / 256, tiles_n = Nj / 256, per_plane = tiles_m * tiles_n, total = per_plane * planes;
+    const int nks = Kl / 32;
+    f32x16_t acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    bf16x8_t va[4], vb[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) va[i][e] = (__bf16)(0.01f * (lane + i + e));
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vb[i][e] = (__bf16)(0.02f * (lane - i - e));
+
+    for (int v = blockIdx.x; v < total; v += gridDim.x) {
+        int lid = v;
+        if ((total & 7) == 0 && (gridDim.x & 7) == 0) lid = (v & 7) * (total >> 3) + (v >> 3);
+        const int p = lid / per_plane, rem = lid - p * per_plane;
+        const int i0 = (rem / tiles_n) * 256, j0 = (rem % tiles_n) * 256;
+        const uint16_t *Ap = A + (size_t)p * Mi * Kl, *Bp = B + (size_t)p * Kl * Nj;
+        for (int s = 0; s < nks; ++s) {
+            const uint32_t slot = lds0 + (uint32_t)(s & 3) * 16384u;
+            if (DMA) {
+                if (!WIDE) {
+                    // [row][l] operand, half lines: instruction q covers rows 16q .. 16q+15, four 16-byte chunks per row
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int q = 2 * wave + j, row = 16 * q + (lane >> 2), c = lane & 3;
+                        dma16(Ap + (size_t)(i0 + row) * Kl + s * 32 + 8 * c, slot + q * 1024);
+                    }
+                } else {
+                    // whole lines: instruction q covers rows 8q .. 8q+7, eight chunks (64 contraction elements) per row;
+                    // the upper half of the rows is fetched in the even stage of a pair, the lower half in the odd one
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int q = 16 * (s & 1) + 2 * wave + j, row = 8 * q + (lane >> 3), c = lane & 7;
+                        dma16(Ap + (size_t)(i0 + row) * Kl + (s & ~1) * 32 + 8 * c, lds0 + (uint32_t)((s >> 1) & 1) * 32768u + q * 1024);
+                    }
+                }
+                // [l][row] operand: instruction q covers contraction rows 2q, 2q+1, 32 chunks (256 columns) per row
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int q = 2 * wave + j, k = 2 * q + (lane >> 5), nc = lane & 31;
+                    dma16(Bp + (size_t)(s * 32 + k) * Nj + j0 + 8 * nc, lds0 + 65536u + (uint32_t)(s & 3) * 16384u + q * 1024);
+                }
+            }
+            if (MFMA) {
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[i & 1], va[i >> 1], acc[i], 0, 0, 0);
+            }
+            // at most three stages of loads in flight per wavefront, as in the library's ring
+            if (DMA) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) t += acc[i][e];
+    if (t == 12345.678f) sink[threadIdx.x] = t;     // keeps the products alive; never true
+}
+
+template <int MODE>
+static float run(const uint16_t *A, const uint16_t *B, int Mi, int Nj, int Kl, int planes, float *sink, int grid, int iters)
+{
+    auto kern = probe_kernel<MODE>;
+    const int smem = 131072;
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return -1.f;
+    hipEvent_t e0, e1;
+    hipEventCreate(&e0);
+    hipEventCreate(&e1);
+    for (int i = 0; i < 3; ++i) hipLaunchKernelGGL(kern, dim3(grid), dim3(512), smem, 0, A, B, Mi, Nj, Kl, planes, sink);
+    hipEventRecord(e0, 0);
+    for (int i = 0; i < iters; ++i) hipLaunchKernelGGL(kern, dim3(grid), dim3(512), smem, 0, A, B, Mi, Nj, Kl, planes, sink);
+    hipEventRecord(e1, 0);
+    if (hipEventSynchronize(e1) != hipSuccess) return -1.f;
+    float ms = 0.f;
+    hipEventElapsedTime(&ms, e0, e1);
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    return ms / iters;
+}
+
+// mode: bit 0 loads, bit 1 MFMAs, bit 2 whole-line loads of the first operand.  A: planes x Mi x Kl, B: planes x Kl x Nj
+// (device pointers, bf16 bit patterns), sink: 512 floats.  Returns milliseconds per launch, negative on error.
+extern "C" float stl_probe_run(int mode, const void *A, const void *B, int Mi, int Nj, int Kl, int planes, void *sink, int grid,
+                               int iters)
+{
+    if (Mi % 256 || Nj % 256 || Kl % 64 || planes < 1 || grid < 1 || iters < 1) return -2.f;
+    const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
+    float *s = (float *)sink;
+    switch (mode) {
+        case 1: return run<1>(a, b, Mi, Nj, Kl, planes, s, grid, iters);
+        case 2: return run<2>(a, b, Mi, Nj, Kl, planes, s, grid, iters);
+        case 3: return run<3>(a, b, Mi, Nj, Kl, planes, s, grid, iters);
+        case 5: return run<5>(a, b, Mi, Nj, Kl, planes, s, grid, iters);
+        case 7: return run<7>(a, b, Mi, Nj, Kl, planes, s, grid, iters);
+    }
+    return -2.f;
+}

@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--sweep-big", action="store_true", help="with --sweep: include n=16384 in the square sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mlp", action="store_true", help="skip the stacked-layer (MLP-shaped pair) leg")
+    ap.add_argument("--variants", action="store_true",
+                    help="also time the three forward variants (three launches, decode in the epilogue, one launch) over a range of shapes")
     ap.add_argument("--extra", action="store_true",
                     help="also time the forward passes of the two-activation and ragged-row entry points")
     ap.add_argument("--profile-only", default="",
@@ -548,6 +550,32 @@ def main():
 
     if args.sweep:
         run_leg("sweep", leg_sweep)
+
+    def leg_variants():
+        """Three-launch, decode-in-epilogue and single-launch forward over shapes from launch-bound to the benchmark shape
+        (median of per-call event times, microseconds)."""
+        table = {}
+        for mm, kk, nn, rr in ((128, 256, 256, 8), (128, 512, 512, 8), (256, 1024, 1024, 8), (256, 1024, 1024, 32),
+                               (512, 1024, 1024, 16), (1024, 1024, 1024, 32), (1024, 4096, 4096, 8), (2048, 2048, 2048, 32),
+                               (8192, 4096, 4096, 8), (8192, 4096, 4096, 32)):
+            Xs, Ws, Es, Ds = rand_problem(mm, kk, nn, rr)
+            pr = stl.Problem(mm, kk, nn, rr, stl.STL_BF16)
+            Cs = torch.empty((mm, nn), dtype=bf, device="cuda")
+            nbs = stl.stl_workspace_bytes(pr, stl.STL_OP_FORWARD, stl.STL_FLAG_UNFUSED)
+            wss = torch.empty(max(nbs, 16), dtype=torch.uint8, device="cuda")
+            row = {}
+            for name, fl in (("auto", stl.STL_FLAG_AUTO), ("unfused", stl.STL_FLAG_UNFUSED), ("epilogue", stl.STL_FLAG_EPILOGUE),
+                             ("fused", stl.STL_FLAG_FUSED)):
+                call = lambda fl=fl: stl.stl_forward(pr, Xs, Ws, Es, Ds, Cs, None, None, wss, nbs, fl)
+                for _ in range(10):
+                    call()
+                row[name] = round(T.dist(call, 100)[0] * 1e3, 1)
+            table[f"{mm}x{kk}x{nn} r={rr}"] = row
+            log(f"  variants {mm}x{kk}x{nn} r={rr}: {row}")
+        out["forward_variants_by_shape_us"] = table
+
+    if args.variants:
+        run_leg("variants", leg_variants)
 
     def leg_cpu_baseline():
         import oracle

@@ -531,6 +531,13 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
     if (!X || !What || !E_X || !D || !C) return fail(STL_ERR_INVALID_ARG, "stl_forward: NULL pointer");
     if (any_misaligned(X, What, E_X, D, C, Xhat_save, Yhat_save))
         return fail(STL_ERR_INVALID_ARG, "stl_forward: pointer not 16-byte aligned");
+    // Automatic choice: the single-launch variant where the whole operator is launch-bound (measured: it wins up to
+    // about four million tile products per plane set, e.g. m = 128, k = n = 512, r = 8: one launch of ~10 us against
+    // three of ~5 us), the three-launch path everywhere else.
+    const FwdWs w_declared = fwd_layout(d, variant);     // the workspace is checked against what the caller asked for
+    if (variant == STL_FLAG_AUTO && !Xhat_save && stl::block_forward_eligible(prob->dtype, d.M, d.K, d.N, d.r) &&
+        (double)d.M * d.K * d.N * d.r <= 4.2e6)
+        variant = STL_FLAG_FUSED;
     if (variant == STL_FLAG_EPILOGUE || variant == STL_FLAG_FUSED) {
         if (!stl::block_forward_eligible(prob->dtype, d.M, d.K, d.N, d.r))
             return fail(STL_ERR_UNSUPPORTED,
@@ -539,7 +546,7 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
             return fail(STL_ERR_UNSUPPORTED, "stl_forward: the fused variant never materialises Xhat (Xhat_save must be NULL)");
     }
     const FwdWs w = fwd_layout(d, variant);
-    st = check_workspace("stl_forward", ws, ws_bytes, w.total);
+    st = check_workspace("stl_forward", ws, ws_bytes, w_declared.total);
     if (st != STL_OK) return st;
     hipStream_t s = (hipStream_t)stream;
     const bool gelu = (flags & STL_FLAG_GELU) != 0;

@@ -11,8 +11,12 @@
 // fp32 accumulators are exchanged through LDS and every thread decodes 4 tiles with D in fp32.
 //
 // Decode needs all planes of a tile in one workgroup, and r accumulator planes leave room for only ~1K output
-// tiles per workgroup, so each operand element fetched from L2 feeds few MACs: this kernel is bound by the
-// L2 -> LDS path, not by MFMA.  It wins where the three-launch path is bound by its HBM round trips (small r).
+// tiles per workgroup, so each operand element fetched from L2 feeds few MACs (16 flop per byte against 128 for a
+// one-plane 256 x 256 block): this kernel is bound by the L2 -> LDS path, not by MFMA, and at every shape where the
+// plane products take a measurable time the three-launch path is faster (6 x at the benchmark shape, where this
+// kernel moves 26 GB through L2 at 20 TB/s, the rate the L2 -> LDS path gives).  It wins only where the whole
+// operator is bound by launch latency: one launch instead of three for problems of a few microseconds, which is
+// where the automatic variant choice uses it.
 #include "stl_kernels.h"
 #include "stl_device.h"
 

@@ -124,7 +124,7 @@ struct GemmDesc {
     int o_rows_per_group() const { return o_pg > 0 ? o_pg : nb * Mi; }
 };
 hipError_t launch_plane_gemm(int dtype, const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s);
-// the slow any-shape path, also used directly for fp32 storage
+// the any-shape path (fp32 MFMA), also used directly for fp32 storage
 hipError_t launch_plane_gemm_generic(int dtype, const GemmDesc &g, const void *A, const void *B, void *Out,
                                      hipStream_t s);
 // bf16 MFMA path; returns false in *ok if the shape is not eligible (caller falls back)

@@ -83,6 +83,7 @@ inline float __uint_as_float(uint32_t u) { float f; memcpy(&f, &u, 4); return f;
 #define __builtin_amdgcn_exp2f(x) exp2f(x)
 #define __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, x, y, z) (c)
 #define __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, x, y, z) (c)
+#define __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, x, y, z) (c)
 typedef short cpu_v4i16 __attribute__((ext_vector_type(4)));
 #define __builtin_amdgcn_ds_read_tr16_b64_v4i16(p) (cpu_v4i16{0, 0, 0, 0})
 // a 16-byte global read (stands in for the LDS-DMA load): touch the bytes so that the sanitizer checks them

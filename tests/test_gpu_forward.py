@@ -220,6 +220,25 @@ def test_forward_block_resident_variants(gu, variant, shape):
     assert gu.rel(C[4 * max(M - 3, 0):, 4 * max(N - 5, 0):], blk) <= 2 * gu.TOL["bf16"]
 
 
+@pytest.mark.parametrize("shape", [(128, 256, 256, 8), (128, 512, 512, 8), (64, 512, 512, 16), (256, 1024, 1024, 8)])
+def test_automatic_variant_choice_on_launch_bound_shapes(gu, shape):
+    """Problems of a few microseconds: the automatic choice takes the single-launch variant up to about four million
+    tile products (and the three-launch path above); either way the result is the operator's, and equal bit for bit
+    to the variant it stands for."""
+    import paper_2503_12211_amd as stl
+    m, k, n, r = shape
+    p = stl_synth.stl_problem(m, k, n, r, seed=611 + m + k, dtype="bf16")
+    ref = planes.forward(p["X"], p["What"], p["E_X"], p["D"])
+    auto = gu.forward(p, "bf16", flags=stl.STL_FLAG_AUTO)
+    gu.check(auto, ref, "bf16", f"auto {shape}")
+    small = (m // 4) * (k // 4) * (n // 4) * r <= 4.2e6
+    same = gu.forward(p, "bf16", flags=stl.STL_FLAG_FUSED if small else stl.STL_FLAG_UNFUSED)
+    assert np.array_equal(auto, same)
+    auto_y, Y = gu.forward(p, "bf16", flags=stl.STL_FLAG_AUTO, save_yhat=True)
+    assert np.array_equal(auto_y, auto)
+    assert gu.rel(Y, planes.forward(p["X"], p["What"], p["E_X"], p["D"], return_yhat=True)[1]) <= gu.TOL["bf16"]
+
+
 def test_forward_variants_agree_at_config2_shape(gu):
     """bf16, m=k=n=4096, r=32: all three forward variants against the plane oracle."""
     import paper_2503_12211_amd as stl

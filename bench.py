@@ -196,7 +196,7 @@ def main():
     dWhat = torch.empty((r, K, N), dtype=torch.float32, device="cuda")
     dE_X = torch.empty((r, 16), dtype=torch.float32, device="cuda")
     dD = torch.empty((r, 16), dtype=torch.float32, device="cuda")
-    nf = stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD, stl.STL_FLAG_AUTO)
+    nf = max(stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD, fl) for fl in (stl.STL_FLAG_AUTO, stl.STL_FLAG_PIPELINED))
     nb = stl.stl_workspace_bytes(prob, stl.STL_OP_BACKWARD)
     ws_f = torch.empty(max(nf, 16), dtype=torch.uint8, device="cuda")
     ws_b = torch.empty(max(nb, 16), dtype=torch.uint8, device="cuda")
@@ -279,7 +279,7 @@ def main():
                 "stages": lambda: (stl.stl_encode_activation(prob, X, E_X, Xhat),
                                    stl.stl_plane_matmul(prob, Xhat, What, Yhat),
                                    stl.stl_decode(prob, Yhat, D, C))}
-        for vname, vflag in (("epilogue", stl.STL_FLAG_EPILOGUE), ("fused", stl.STL_FLAG_FUSED)):
+        for vname, vflag in (("epilogue", stl.STL_FLAG_EPILOGUE), ("fused", stl.STL_FLAG_FUSED), ("pipelined", stl.STL_FLAG_PIPELINED)):
             legs[vname] = (lambda vflag=vflag: stl.stl_forward(prob, X, What, E_X, D, C, None, None, ws_f, nf, vflag))
         if args.profile_only == "mlp":
             legs["mlp"] = mlp_setup()[1]["one_pass"]
@@ -437,7 +437,8 @@ def main():
 
     # the other forward variants at the same workload (STL_FLAG_AUTO runs the three-launch path)
     variants = {}
-    for name, flag in (("unfused", stl.STL_FLAG_UNFUSED), ("epilogue", stl.STL_FLAG_EPILOGUE), ("fused", stl.STL_FLAG_FUSED)):
+    for name, flag in (("unfused", stl.STL_FLAG_UNFUSED), ("epilogue", stl.STL_FLAG_EPILOGUE), ("fused", stl.STL_FLAG_FUSED),
+                       ("pipelined", stl.STL_FLAG_PIPELINED)):
         try:
             nv = stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD, flag)
             assert nv <= nf

@@ -15,7 +15,7 @@ _LIB_PATH = Path(os.environ.get("STL_LIBRARY", _HERE / "libstl_mi355x.so"))   # 
 
 STL_F32, STL_BF16 = 0, 1
 STL_OP_ENCODE_WEIGHT, STL_OP_FORWARD, STL_OP_BACKWARD, STL_OP_ENCODE_WEIGHT_BACKWARD = 0, 1, 2, 3
-STL_FLAG_AUTO, STL_FLAG_UNFUSED, STL_FLAG_EPILOGUE, STL_FLAG_FUSED = 0, 1, 2, 3
+STL_FLAG_AUTO, STL_FLAG_UNFUSED, STL_FLAG_EPILOGUE, STL_FLAG_FUSED, STL_FLAG_PIPELINED = 0, 1, 2, 3, 4
 STL_FLAG_GELU = 0x100
 STL_FLAG_B_TRANSPOSED = 0x200
 

@@ -80,7 +80,7 @@ stl_status_t check_workspace(const char *fn, const void *ws, size_t ws_bytes, si
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct FwdWs {
-    size_t xhat, yhat, total;
+    size_t xhat, yhat, ctr, total;
 };
 
 int variant_of(int flags) { return flags & STL_FLAG_VARIANT_MASK; }
@@ -89,7 +89,7 @@ stl_status_t check_flags(int flags, int *variant)
 {
     if (flags & ~(STL_FLAG_VARIANT_MASK | STL_FLAG_GELU)) return fail(STL_ERR_UNSUPPORTED, "unknown flag bits 0x%x", flags);
     int v = variant_of(flags);
-    if (v > STL_FLAG_FUSED) return fail(STL_ERR_UNSUPPORTED, "unknown forward variant %d", v);
+    if (v > STL_FLAG_PIPELINED) return fail(STL_ERR_UNSUPPORTED, "unknown forward variant %d", v);
     *variant = v;
     return STL_OK;
 }
@@ -101,7 +101,10 @@ FwdWs fwd_layout(const Dims &d, int variant)
     w.xhat = off;
     if (variant != STL_FLAG_FUSED) off += align256((size_t)d.r * d.Mp() * d.K * d.es);
     w.yhat = off;
-    if (variant == STL_FLAG_AUTO || variant == STL_FLAG_UNFUSED) off += align256((size_t)d.r * d.Mp() * d.N * d.es);
+    if (variant == STL_FLAG_AUTO || variant == STL_FLAG_UNFUSED || variant == STL_FLAG_PIPELINED)
+        off += align256((size_t)d.r * d.Mp() * d.N * d.es);
+    w.ctr = off;                                        // item counters of the single-launch pipelined forward
+    if (variant == STL_FLAG_PIPELINED) off += align256(stl::forward_pipeline_counter_bytes(d.M));
     w.total = off;
     return w;
 }
@@ -538,6 +541,9 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
     if (variant == STL_FLAG_AUTO && !Xhat_save && stl::block_forward_eligible(prob->dtype, d.M, d.K, d.N, d.r) &&
         (double)d.M * d.K * d.N * d.r <= 4.2e6)
         variant = STL_FLAG_FUSED;
+    if (variant == STL_FLAG_PIPELINED && !stl::forward_pipeline_eligible(prob->dtype, d.M, d.K, d.N, d.r))
+        return fail(STL_ERR_UNSUPPORTED,
+                    "stl_forward: the pipelined variant needs bf16 storage, r <= 32, k and n multiples of 256, n >= 1024 and m >= 2048");
     if (variant == STL_FLAG_EPILOGUE || variant == STL_FLAG_FUSED) {
         if (!stl::block_forward_eligible(prob->dtype, d.M, d.K, d.N, d.r))
             return fail(STL_ERR_UNSUPPORTED,
@@ -564,6 +570,11 @@ stl_status_t stl_forward(const stl_problem_t *prob, const void *X, const void *W
         return STL_OK;
     }
     void *yhat = Yhat_save ? Yhat_save : (void *)(base + w.yhat);
+    if (variant == STL_FLAG_PIPELINED) {
+        STL_HIP(stl::launch_forward_pipeline(X, E_X, What, D, xhat, yhat, C, base + w.ctr, d.M, d.K, d.N, d.r, gelu, s),
+                "forward/pipelined");
+        return STL_OK;
+    }
     return forward_three_launch(prob, d, X, What, E_X, D, C, xhat, yhat, !Xhat_save && !Yhat_save, gelu, s);
 }
 

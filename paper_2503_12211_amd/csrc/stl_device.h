@@ -28,6 +28,19 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
 
+// 16-byte store that is written through the XCD's L2 to memory (cache-coherence bits sc0 sc1: system scope), for data that
+// workgroups on another XCD read later in the same launch: when the store has completed (vmcnt) the data is where every
+// L2 fetches from, with no write-back of the whole cache.  THROUGH = false is the ordinary store.
+template <bool THROUGH>
+__device__ __forceinline__ void store16(void *p, u32x4_t v)
+{
+    if constexpr (THROUGH) {
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+    } else {
+        *reinterpret_cast<u32x4_t *>(p) = v;
+    }
+}
+
 // storage-type traits: load as fp32, store from fp32
 template <typename T> struct Elem;
 template <> struct Elem<float> {

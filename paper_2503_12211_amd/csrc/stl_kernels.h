@@ -134,6 +134,14 @@ hipError_t launch_plane_gemm_mfma(const GemmDesc &g, const void *A, const void *
 bool plane_gemm_pipe_eligible(const GemmDesc &g);
 hipError_t launch_plane_gemm_pipe(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s);
 
+// The whole forward pass as one persistent launch: encode and decode items run on some CUs while the plane products
+// run on the others (bf16, r <= 32; see stl_pipeline.hip).  `counters` is forward_pipeline_counter_bytes(M) bytes of
+// scratch (cleared by the launch itself).  Results are bit-identical to encode -> plane products -> decode.
+bool forward_pipeline_eligible(int dtype, int M, int K, int N, int r);
+size_t forward_pipeline_counter_bytes(int M);
+hipError_t launch_forward_pipeline(const void *X, const void *E, const void *What, const void *Dm, void *Xhat, void *Yhat,
+                                   void *C, void *counters, int M, int K, int N, int r, bool gelu, hipStream_t s);
+
 // Forward on one output block with all planes resident (decode in the epilogue).  encode_in_kernel: Xin is X
 // (single-launch fused form); otherwise Xin is Xhat.  Ysave may be NULL.  bf16 storage only.
 bool block_forward_eligible(int dtype, int M, int K, int N, int r);

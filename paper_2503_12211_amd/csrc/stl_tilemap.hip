@@ -3,6 +3,7 @@
 // through HBM; arithmetic is fp32.
 #include "stl_kernels.h"
 #include "stl_device.h"
+#include "stl_tile_items.h"
 
 
 namespace stl {
@@ -324,8 +325,6 @@ __global__ __launch_bounds__(256) void outer_mfma_kernel(const bf16_t *__restric
 // every lane 4 consecutive planes of its tile (the MFMA B fragment).  The accumulator leaves each
 // lane with one row of one output tile (4 entries = 8 bytes), so 16 lanes store 128 contiguous bytes.
 // ---------------------------------------------------------------------------------------
-typedef short v4i16_t __attribute__((ext_vector_type(4)));
-
 // OUTER: the same pass also accumulates the basis gradient G (r x 16) += P (r x tiles) . tileview(V) (tiles x 16)
 // (dE_X with P = dXhat, V = X while dX is decoded), so that the planes are read from HBM once for both results;
 // every block writes one partial to `part`, added up in block order by outer_final_kernel.
@@ -339,153 +338,14 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(const bf16_t *__restri
     __shared__ __align__(16) char slab_all[4][KC * 32 * ROWB];
     // OUTER: per wavefront the 64 tiles of V, tile-major [tile][16 entries] (32 bytes per tile)
     __shared__ __align__(16) char sT_all[OUTER ? 4 : 1][OUTER ? 64 * 32 : 16];
-    const int ngroups = (r + 15) >> 4;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int j = lane & 15, kq = lane >> 4;
     f32x4_t oacc[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) oacc[g] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    char *slab = slab_all[wave];
-    char *sT = sT_all[OUTER ? wave : 0];
-    const int j = lane & 15, kq = lane >> 4;
-    // row of tile `lane` in sT: rows t and t^4 are swapped where bit 3 of t is set, so that the four 4-tile groups one
-    // transposing read touches fall into both halves of the banks
-    const int strow = lane ^ (((lane >> 3) & 1) << 2);
-
-    // A fragments: lane (entry q = j, kq) holds D[32g + 8kq + e][q], e = 0..7
-    bf16x8_t fa[KC];
-#pragma unroll
-    for (int g = 0; g < KC; ++g) {
-        uint32_t w[4];
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-            const int p0 = 32 * g + 8 * kq + 2 * e2;
-            const uint32_t lo = p0 < r ? Dm[p0 * 16 + j] : 0u, hi = p0 + 1 < r ? Dm[(p0 + 1) * 16 + j] : 0u;
-            w[e2] = lo | (hi << 16);
-        }
-        fa[g] = __builtin_bit_cast(bf16x8_t, u32x4_t{w[0], w[1], w[2], w[3]});
-    }
-    // swizzle of the 16-byte chunk index inside a row, so that the 8 plane rows one transposing read touches
-    // (planes 0-3 and 8-11, or 4-7 and 12-15, of a 16-tile column group) fall into different bank windows
-    auto swz = [](int row) { return ((((row >> 1) & 1) | (((row >> 3) & 1) << 1)) << 1); };
-
-    const size_t plane = (size_t)pg * Cc;
-    const size_t ld = (size_t)Cc * 4;
-    const long items = (long)R * chunks;
-    // (tile row, chunk) of this wavefront's item, advanced without a division per round
-    const long stride = (long)gridDim.x * 4;
-    int In = (int)(((long)blockIdx.x * 4 + wave) / chunks), ckn = (int)(((long)blockIdx.x * 4 + wave) % chunks);
-    const int dI = (int)(stride / chunks), dck = (int)(stride % chunks);
-
-    // Loader role of a lane: plane 8*g8 + pr, 16-byte chunk ch (8 tiles) -- whole 128-byte lines, 8 planes per
-    // instruction; with OUTER also tile J0 + lane of V (4 rows x 8 bytes).  The NEXT item's operands are fetched into
-    // registers while the current item is computed and stored.
-    const int pr = lane >> 3, ch = lane & 7;
-    u32x4_t pre[KC * 4];
-    u32x2_t xpre[OUTER ? 4 : 1];
-    auto fetch = [&](int Ii, int cki) {
-        const int Jl = cki * 64 + 8 * ch;
-        const int Ia = Ii < R ? rm.tile_row(Ii) : 0;        // Ii counts the tile rows of this launch, Ia is the tile row itself
-        const size_t rowb = plane_row_base(Ia, pg, r, Cc);
-#pragma unroll
-        for (int g8 = 0; g8 < KC * 4; ++g8) {
-            const int pl = 8 * g8 + pr;
-            u32x4_t v = {0u, 0u, 0u, 0u};       // planes >= r stay zero (they meet zero D entries, but must be finite)
-            if (Ii < R && pl < r && Jl < Cc) v = *reinterpret_cast<const u32x4_t *>(P + rowb + (size_t)pl * plane + Jl);
-            pre[g8] = v;
-        }
-        if (OUTER) {
-            const int Jt = cki * 64 + lane, nv = rm.valid(Ia);
-            const size_t r0 = rm.row0(Ia);
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                u32x2_t xv = {0u, 0u};
-                if (Ii < R && Jt < Cc && a < nv) xv = *reinterpret_cast<const u32x2_t *>(V + (r0 + a) * ld + (size_t)Jt * 4);
-                xpre[a] = xv;
-            }
-        }
-    };
-    fetch(In, ckn);
-
-    for (long item0 = (long)blockIdx.x * 4; item0 < items; item0 += stride) {
-        const int J0 = ckn * 64;
-        const bool live = In < R;
-        const int I = live ? rm.tile_row(In) : 0;
-        // slab and sV belong to this wavefront alone and its LDS operations execute in order: the writes below land
-        // after the previous round's fragment reads without a workgroup barrier (which would also make the wavefront
-        // wait for the loads it is about to put in flight)
-#pragma unroll
-        for (int g8 = 0; g8 < KC * 4; ++g8) {
-            const int pl = 8 * g8 + pr;
-            *reinterpret_cast<u32x4_t *>(slab + pl * ROWB + ((ch ^ swz(pl)) << 4)) = pre[g8];
-        }
-        if (OUTER) {
-            // lane = tile J0 + lane: its 16 entries (4 rows x 8 bytes) as two 16-byte writes, tile-major; they come back
-            // as "entry x 4 consecutive tiles" through the transposing read below
-            *reinterpret_cast<u32x4_t *>(sT + strow * 32) = u32x4_t{xpre[0][0], xpre[0][1], xpre[1][0], xpre[1][1]};
-            *reinterpret_cast<u32x4_t *>(sT + strow * 32 + 16) = u32x4_t{xpre[2][0], xpre[2][1], xpre[3][0], xpre[3][1]};
-        }
-        In += dI;
-        ckn += dck;
-        if (ckn >= chunks) { ckn -= chunks; ++In; }
-        if (item0 + stride < items) fetch(In, ckn);
-        if (live && OUTER) {
-            // K = 32 tiles per MFMA: A = planes x tiles from the slab (lane: plane 16g + j, tiles 32s + 8kq ..),
-            // B = tiles x entries from sT (lane: entry j, same tiles)
-#pragma unroll
-            for (int sx = 0; sx < 2; ++sx) {
-                v4i16_t tb[2];
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    // source address of this lane inside its 16-lane group: tile row (32sx + 8kq + 4h) + j/4, entries 4*(j%4)..
-                    const int t0 = 32 * sx + 8 * kq + 4 * h;
-                    const int row = (t0 ^ (((t0 >> 3) & 1) << 2)) + (j >> 2);
-                    tb[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t *)(
-                        (__attribute__((address_space(3))) char *)(sT + row * 32 + 8 * (j & 3))));
-                }
-                struct { v4i16_t a, b; } both_b = {tb[0], tb[1]};
-                const bf16x8_t fb = __builtin_bit_cast(bf16x8_t, both_b);
-#pragma unroll
-                for (int g = 0; g < 2 * KC; ++g) {
-                    if (g < ngroups) {
-                        const int pl = 16 * g + j;
-                        const bf16x8_t fp = *reinterpret_cast<const bf16x8_t *>(slab + pl * ROWB + (((4 * sx + kq) ^ swz(pl)) << 4));
-                        oacc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fp, fb, oacc[g], 0, 0, 0);
-                    }
-                }
-            }
-        }
-        if (live) {
-            const int nv_out = rm.valid(I);
-            const size_t r0_out = rm.row0(I);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {                   // 16 tiles per MFMA
-                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int g = 0; g < KC; ++g) {
-                    v4i16_t t[2];
-#pragma unroll
-                    for (int kk = 0; kk < 2; ++kk) {
-                        // source row for this lane of the 16-lane group: plane 32g + 8kq + 4kk + j/4, tiles 16u + 4(j%4)
-                        const int row = 32 * g + 8 * kq + 4 * kk + (j >> 2);
-                        const int col = 16 * u + 4 * (j & 3);
-                        const char *src = slab + row * ROWB + ((((col >> 3)) ^ swz(row)) << 4) + ((col & 7) << 1);
-                        t[kk] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t *)(
-                            (__attribute__((address_space(3))) char *)src));
-                    }
-                    struct { v4i16_t a, b; } both = {t[0], t[1]};
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[g], __builtin_bit_cast(bf16x8_t, both), acc, 0, 0, 0);
-                }
-                // lane holds row a = kq of tile J0 + 16u + j: entries acc[0..3]
-                const int J = J0 + 16 * u + j;
-                if (J < Cc && kq < nv_out) {
-                    float c0 = acc[0], c1 = acc[1], c2 = acc[2], c3 = acc[3];
-                    if (GELU) { c0 = gelu_erf(c0); c1 = gelu_erf(c1); c2 = gelu_erf(c2); c3 = gelu_erf(c3); }
-                    const u32x2_t w = {pack_bf16x2(c0, c1), pack_bf16x2(c2, c3)};
-                    *reinterpret_cast<u32x2_t *>(Cmat + (r0_out + kq) * ld + (size_t)J * 4) = w;
-                }
-            }
-        }
-    }
+    // wavefront w of block b takes items 4b + w, 4b + w + 4 * gridDim.x, ...
+    decode_items<GELU, KC, OUTER>(P, Dm, Cmat, R, Cc, r, chunks, V, pg, rm, (long)blockIdx.x * 4 + wave, (long)gridDim.x * 4,
+                                  (long)R * chunks, sT_all[OUTER ? wave : 0], slab_all[wave], oacc, lane);
     if (OUTER) {
         // accumulator e of group g: plane 16g + 4*kq + e, tile entry j; fixed-order sum over the four wavefronts
         __syncthreads();

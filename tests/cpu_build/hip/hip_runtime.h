@@ -101,3 +101,11 @@ inline void cpu_touch16(const void *g, uint32_t lds)
 }
 inline void cpu_touch16(const void *g) { if ((uintptr_t)g & 15) { fprintf(stderr, "runtime error: LDS-DMA source %p is not 16-byte aligned (%s)\n", g, g_kernel_name); abort(); } volatile uint64_t a = ((const volatile uint64_t *)g)[0], b = ((const volatile uint64_t *)g)[1]; (void)a; (void)b; }
 #define __builtin_amdgcn_sched_group_barrier(a, b, c) ((void)0)
+// agent-scope atomics, fences and sleeps of the kernels that synchronise workgroups through counters: threads run one
+// after the other here, so a counter that is waited for always reads as reached
+#define __HIP_MEMORY_SCOPE_AGENT 0
+#define __hip_atomic_load(p, order, scope) (0xffffffffu)
+#define __hip_atomic_fetch_add(p, v, order, scope) (*(p) += (v), *(p) - (v))
+#define __hip_atomic_fetch_or(p, v, order, scope) (*(p) |= (v))
+#define __builtin_amdgcn_fence(order, scope) ((void)0)
+#define __builtin_amdgcn_s_sleep(n) ((void)0)

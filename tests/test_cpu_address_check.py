@@ -30,15 +30,20 @@ def _host_source(text: str) -> str:
     16-byte read the sanitizer can see whose LDS destination is checked against the dynamic LDS size of the launch, hardware
     waits and barriers nothing."""
     text = text.replace("extern __shared__ __align__(16) char smem[];", "char *smem = cpu_dyn_lds_ptr();")
-    assert "global_load_lds" not in text or DMA in text, "LDS-DMA statement changed: update the host form"
+    assert "global_load_lds_dwordx4 %0" not in text or DMA in text, "LDS-DMA statement changed: update the host form"
     text = text.replace(DMA, "cpu_touch16(g, l);")
     # LDS addresses count from the start of the dynamic array in the host form
     for macro in ("STL_LDS", "STL_LDS_PTR"):
         text = text.replace(f"(uint32_t)(uintptr_t){macro}(smem)", "0u")
     text = re.sub(r'asm volatile\("s_barrier" ::: "memory"\);', ";", text)
     text = re.sub(r'asm volatile\("s_waitcnt [^;]*;', ";", text)
+    text = re.sub(r'asm volatile\("" : "\+v"\(\w+\)\);', ";", text)      # opaque-value fences
+    text = text.replace('asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");',
+                        "*reinterpret_cast<u32x4_t *>(p) = v;")               # write-through store: a plain store on the host
     left = [ln for ln in text.splitlines() if "asm volatile" in ln and 'asm volatile("" :::' not in ln]
     assert not left, f"unhandled inline assembly: {left}"
+    if "STL_PIPELINE_STATIC_TICKETS" in text:
+        text = "#define STL_PIPELINE_STATIC_TICKETS 1\n" + text
     return text.replace('#include "../../include/stl.h"', '#include "stl.h"')
 
 
@@ -84,7 +89,8 @@ def test_planted_overflow_is_reported(checker):
 
 def test_core_path_addresses(checker):
     checker("bwd:512:256:384:32", "bwd:1024:1024:1024:49", "bwd:260:36:44:7", "f32,bwd:64:32:48:17",
-            "fwd:1024:512:512:32:2", "fwd:1024:512:512:16:3", "fwd:8192:4096:256:8:0",
+            "fwd:1024:512:512:32:2", "fwd:1024:512:512:16:3", "fwd:8192:4096:256:8:0", "fwd:2048:1024:1024:32:4",
+            "fwd:2340:256:1024:17:4",
             "mlp:1024:256:1024:24", "mlp:64:40:36:9", "ewb:256:384:24", "ewb:64:36:8", "f32,ewb:96:160:17")
 
 

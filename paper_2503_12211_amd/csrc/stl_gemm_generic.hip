@@ -106,6 +106,7 @@ hipError_t launch_plane_gemm_generic(int dtype, const GemmDesc &g, const void *A
 
 hipError_t launch_plane_gemm(int dtype, const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s)
 {
+    if (dtype == 1 && plane_gemm_wide_eligible(g)) return launch_plane_gemm_wide(g, A, B, Out, s);
     if (dtype == 1 && plane_gemm_pipe_eligible(g)) return launch_plane_gemm_pipe(g, A, B, Out, s);
     if (dtype == 1 && plane_gemm_mfma_eligible(g)) return launch_plane_gemm_mfma(g, A, B, Out, s);
     return launch_plane_gemm_generic(dtype, g, A, B, Out, s);

@@ -100,6 +100,77 @@ struct Src {
     }
 };
 
+
+// ---- whole-line form of a [row][l] operand ------------------------------------------------------------------------------
+// A [row][l] operand fetched 32 contraction elements at a time asks L2 for half a 128-byte line per row and stage, and
+// for the other half one stage later: twice the requests for the same bytes (counted: TCC_REQ).  In the whole-line
+// form an LDS slot holds 64 contraction elements of every row (128 bytes = one line per row, ROWS * 128 bytes per slot)
+// and serves two stages; it is filled in two halves of ROWS / 2 rows, one half per stage, so that every stage still
+// issues the same number of instructions.  Three slots: while pair j is multiplied, pair j+1 has landed and pair j+2
+// is in flight.
+// LDS: row stride 128 bytes; 16-byte chunk c of row `row` lies at chunk position c ^ ((row >> 1) & 7): the sixteen
+// rows of one ds_read_b128 access phase ({0-3, 12-15, 20-23, 24-27} or {4-11, 16-19, 28-31}, see above) then fall
+// on sixteen different (row parity, chunk position) pairs, i.e. on all 64 banks once.
+__device__ __forceinline__ int wswz(int row) { return (row >> 1) & 7; }
+
+template <int ROWS, int NW>
+struct SrcWide {
+    static constexpr int HALF = ROWS / 2;                   // rows per half slot
+    static constexpr int NI = HALF / 8 / NW;                // instructions per wavefront and half (8 rows x 128 bytes each)
+    static constexpr int SLOT_BYTES = ROWS * 128, HALF_BYTES = HALF * 128;
+    const bf16_t *p[2][NI];
+    __device__ __forceinline__ void init(const bf16_t *base, long ld, int row0, int rows_total, int wave, int lane, int plane,
+                                         int batch, int pg, int roff)
+    {
+        const size_t poff = (size_t)plane * pg * ld;
+#pragma unroll
+        for (int hp = 0; hp < 2; ++hp)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int q = NI * wave + j;
+                const int row = HALF * hp + 8 * q + (lane >> 3), c = (lane & 7) ^ wswz(row);
+                int gr = row0 + row;
+                gr = gr < rows_total ? gr : rows_total - 1;   // rows past the edge feed only discarded outputs
+                p[hp][j] = base + plane_row_base(roff + gr, pg, batch, (int)ld) + poff + 8 * c;
+            }
+    }
+    // instruction j of half HP into the slot at LDS byte address `slot`
+    template <int HP>
+    __device__ __forceinline__ void issue_one(uint32_t slot, int wave, int j)
+    {
+        dma16(p[HP][j], slot + HP * HALF_BYTES + (NI * wave + j) * 1024);
+    }
+    template <int HP>
+    __device__ __forceinline__ void next_pair()               // after the last instruction of half HP: 64 elements on
+    {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) p[HP][j] += 64;
+    }
+    template <int HP>
+    __device__ __forceinline__ void issue_half(uint32_t slot, int wave)
+    {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) issue_one<HP>(slot, wave, j);
+        next_pair<HP>();
+    }
+};
+
+template <int ROWS>
+struct FragWide {
+    int off[2];     // [ks], for the first stage of a pair; the second stage's chunks are 4 further: off ^ 64
+    __device__ __forceinline__ void init(int tile_row0, int lane)
+    {
+        const int h = lane >> 5, row = tile_row0 + (lane & 31);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) off[ks] = row * 128 + (((2 * ks + h) ^ wswz(row)) << 4);
+    }
+    // fragment f (32 rows further per f) of k16-step ks of stage parity sp, from the slot that holds the stage's pair
+    __device__ __forceinline__ bf16x8_t read(const char *slot, int f, int ks, int sp) const
+    {
+        return *reinterpret_cast<const bf16x8_t *>(slot + (off[ks] ^ (sp << 6)) + f * 32 * 128);
+    }
+};
+
 // Fragment addressing: byte offset inside one operand stage for MFMA rows (frag_row0 + lane%32), k16-step ks.
 template <bool KMAJOR, int SWZ, int ROWS>
 struct Frag {
@@ -196,6 +267,7 @@ template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
     if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if constexpr (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
     else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     else if constexpr (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
     else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");

@@ -142,6 +142,10 @@ size_t forward_pipeline_counter_bytes(int M);
 hipError_t launch_forward_pipeline(const void *X, const void *E, const void *What, const void *Dm, void *Xhat, void *Yhat,
                                    void *C, void *counters, int M, int K, int N, int r, bool gelu, hipStream_t s);
 
+// the same with the first ([row][l]) operand fetched as whole 128-byte lines (contraction a multiple of 64, one problem)
+bool plane_gemm_wide_eligible(const GemmDesc &g);
+hipError_t launch_plane_gemm_wide(const GemmDesc &g, const void *A, const void *B, void *Out, hipStream_t s);
+
 // Forward on one output block with all planes resident (decode in the epilogue).  encode_in_kernel: Xin is X
 // (single-launch fused form); otherwise Xin is Xhat.  Ysave may be NULL.  bf16 storage only.
 bool block_forward_eligible(int dtype, int M, int K, int N, int r);

@@ -36,6 +36,31 @@ def test_forward_backward_random_shapes(gu, m, k, n, r, seed, dtype):
         assert gu.rel(got[name], g) <= gu.TOL[dtype], name
 
 
+@settings(max_examples=30, deadline=None, database=None, suppress_health_check=[HealthCheck.function_scoped_fixture])
+@given(m=dims, k=dims, n=dims, r=st.integers(1, 64), seed=st.integers(0, 2 ** 31 - 1), dtype=st.sampled_from(["f32", "bf16"]))
+def test_forward_and_input_gradient_fresh_draws_entrywise_bound(gu, m, k, n, r, seed, dtype):
+    """Fresh examples on every run, against a bound that holds for EVERY draw: the roundings of the path (encoded operand,
+    encoded product, output: relative 2^-9 each for bf16; fp32 accumulation over the contraction and the planes) bound the
+    error of an entry by a multiple of the same expression evaluated on absolute values,
+        |C - C_exact| <= (3 u + (K + r + 24) 2^-24) * decode_|D|( encode_|E_X|(|X|) . |What| ),
+    however much the signed sums cancel (which is what makes a relative-norm bar unsafe for tiny random shapes).  The same
+    for dX with (D, dC) as encoder and input, What transposed, and E_X as decoder."""
+    from oracle import planes
+    p = stl_synth.stl_problem(m, k, n, r, seed=seed, dtype=dtype, with_dC=True)
+    u = 2.0 ** -9 if dtype == "bf16" else 2.0 ** -24
+    a = {k_: np.abs(np.asarray(v, dtype=np.float64)) for k_, v in p.items()}
+    C = gu.forward(p, dtype)
+    ref = oracle.forward(p["X"], p["What"], p["E_X"], p["D"])
+    S = planes.decode(planes.plane_products(planes.encode(a["X"], a["E_X"]), a["What"]), a["D"])
+    c = 3 * u * 1.01 + (k // 4 + r + 24) * 2.0 ** -24
+    assert np.all(np.abs(C - ref) <= c * S + 1e-30), float(np.max(np.abs(C - ref) / (c * S + 1e-30)))
+    dX = gu.backward(p, dtype, skip=("dWhat", "dE_X", "dD"))["dX"]
+    dX_ref = oracle.backward(p["X"], p["What"], p["E_X"], p["D"], p["dC"])[0]
+    S2 = planes.decode(planes.plane_products(planes.encode(a["dC"], a["D"]), a["What"].transpose(0, 2, 1)), a["E_X"])
+    c2 = 3 * u * 1.01 + (n // 4 + r + 24) * 2.0 ** -24
+    assert np.all(np.abs(dX - dX_ref) <= c2 * S2 + 1e-30), float(np.max(np.abs(dX - dX_ref) / (c2 * S2 + 1e-30)))
+
+
 def test_fp32_bilinearity_and_rank_additivity(gu):
     """fp32 path: f(aX1+bX2) = a f(X1) + b f(X2); planes [0,r1) plus planes [r1,r) add up to all planes."""
     rng = np.random.default_rng(5)

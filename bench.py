@@ -401,7 +401,7 @@ def main():
             "decode": {"ms": round(ms_dec_cold, 5), "GBps": round(dec_bytes / ms_dec_cold / 1e6, 1),
                        "frac_hbm_peak": round(dec_bytes / ms_dec_cold / 1e6 / PEAK_HBM_GBS, 4)},
         },
-        "roofline": {"kernel": "gemm_pipe_kernel (forward plane products Yhat[p] = Xhat[p] What[p], one launch, "
+        "roofline": {"kernel": "gemm_pipe_wide_kernel<true> (forward plane products Yhat[p] = Xhat[p] What[p], one launch, "
                                "2*r*M*K*N flops)", "bound": "mfma",
                      "achieved": round(tf(gemm_flop, ms_gemm), 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tf(gemm_flop, ms_gemm) / PEAK_BF16_TFLOPS, 4),

@@ -99,6 +99,8 @@ def test_tall_matrix_stays_within_grid_limits(checker):
     matrix-core kernel takes): every launch extent must stay within the device limits, which the stand-in runtime
     checks for every launch, and every access in bounds."""
     checker("f32,bwd:4200000:8:8:2", "bwd:4200000:4:12:3")
+    # the shapes of the GPU parity test on tall matrices (tests/test_gpu_backward.py)
+    checker("bwd:560000:32:32:8", "f32,bwd:560004:8:8:2", "bwd:560004:24:8:5")
 
 
 def test_two_activation_addresses(checker):

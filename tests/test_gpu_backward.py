@@ -158,3 +158,23 @@ def test_step_mid_size_every_entry(gu, dtype):
     ref = oracle_grads(p, use_planes=True)
     for name in NAMES:
         gu.check(got[name], ref[name], dtype, name)
+
+
+@pytest.mark.parametrize("dtype,shape", [("f32", (560004, 8, 8, 2)), ("bf16", (560000, 32, 32, 8)), ("bf16", (560004, 24, 8, 5))])
+def test_tall_matrix_beyond_one_grid_extent(gu, dtype, shape):
+    """More tile rows (140 000) than a grid extent holds (65 535): the row loops of the tile maps and of the any-shape plane
+    products wrap around.  Forward and backward, every entry of C and dX sampled by whole row blocks, all of the small
+    gradients; the oracle runs on the sampled rows only (rows are independent in C and dX) and on all rows for the sums."""
+    m, k, n, r = shape
+    p = stl_synth.stl_problem(m, k, n, r, seed=77, dtype=dtype, with_dC=True)
+    res = gu.step(p, dtype)
+    ref = dict(zip(NAMES, planes.backward(p["X"], p["What"], p["E_X"], p["D"], p["dC"])))
+    C_ref = planes.forward(p["X"], p["What"], p["E_X"], p["D"])
+    tol = gu.TOL[dtype]
+    for lo in (0, 4 * 32768 - 8, 4 * 65535 - 8, 4 * 65536, 4 * 131072 - 4, m - 16):
+        sl = slice(lo, lo + 16)
+        assert gu.rel(res["C"][sl], C_ref[sl]) <= tol, ("C", lo)
+        assert gu.rel(res["dX"][sl], ref["dX"][sl]) <= tol, ("dX", lo)
+    assert gu.rel(res["C"], C_ref) <= tol and gu.rel(res["dX"], ref["dX"]) <= tol
+    for name in ("dWhat", "dE_X", "dD"):
+        assert gu.rel(res[name], ref[name]) <= tol, name

@@ -99,6 +99,110 @@ __global__ __launch_bounds__(512) void probe_kernel(const uint16_t *__restrict__
     if (t == 12345.678f) sink[threadIdx.x] = t;     // keeps the products alive; never true
 }
 
+// Second form of the probe: whole-line loads only, with the number of load instructions a wavefront may leave in flight
+// at the end of a stage (DEPTH, four instructions per stage), the placement of the loads (SPREAD: one after every fourth
+// MFMA instead of all four in front of the stage's MFMAs) and a workgroup barrier per stage (BAR) as parameters.
+template <int MODE, int DEPTH, int SPREAD, int BAR>
+__global__ __launch_bounds__(512) void probe_depth_kernel(const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int Mi,
+                                                          int Nj, int Kl, int planes, float *__restrict__ sink)
+{
+    constexpr bool DMA = MODE & 1, MFMA = MODE & 2;
+    extern __shared__ __align__(16) char smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tiles_m = Mi / 256, tiles_n = Nj / 256, per_plane = tiles_m * tiles_n, total = per_plane * planes;
+    const int nks = Kl / 32;
+    f32x16_t acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    bf16x8_t va[4], vb[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) va[i][e] = (__bf16)(0.01f * (lane + i + e));
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vb[i][e] = (__bf16)(0.02f * (lane - i - e));
+
+    for (int v = blockIdx.x; v < total; v += gridDim.x) {
+        int lid = v;
+        if ((total & 7) == 0 && (gridDim.x & 7) == 0) lid = (v & 7) * (total >> 3) + (v >> 3);
+        const int p = lid / per_plane, rem = lid - p * per_plane;
+        const int i0 = (rem / tiles_n) * 256, j0 = (rem % tiles_n) * 256;
+        const uint16_t *Ap = A + (size_t)p * Mi * Kl, *Bp = B + (size_t)p * Kl * Nj;
+        for (int s = 0; s < nks; ++s) {
+            const uint16_t *src[4];
+            uint32_t dst[4];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {   // whole lines of the [row][l] operand
+                const int q = 16 * (s & 1) + 2 * wave + j, row = 8 * q + (lane >> 3), c = lane & 7;
+                src[j] = Ap + (size_t)(i0 + row) * Kl + (s & ~1) * 32 + 8 * c;
+                dst[j] = lds0 + (uint32_t)((s >> 1) & 1) * 32768u + q * 1024;
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int q = 2 * wave + j, k = 2 * q + (lane >> 5), nc = lane & 31;
+                src[2 + j] = Bp + (size_t)(s * 32 + k) * Nj + j0 + 8 * nc;
+                dst[2 + j] = lds0 + 65536u + (uint32_t)(s & 3) * 16384u + q * 1024;
+            }
+            if (DMA && !SPREAD) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) dma16(src[j], dst[j]);
+            }
+            if (MFMA) {
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[i & 1], va[i >> 1], acc[i], 0, 0, 0);
+                        if (SPREAD) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (DMA && (i & 3) == 1) {
+                                dma16(src[ks * 2 + (i >> 2)], dst[ks * 2 + (i >> 2)]);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                    }
+            } else if (DMA && SPREAD) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) dma16(src[j], dst[j]);
+            }
+            if (DMA) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DEPTH) : "memory");
+            if (BAR) asm volatile("s_barrier" ::: "memory");
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) t += acc[i][e];
+    if (t == 12345.678f) sink[threadIdx.x] = t;     // keeps the products alive; never true
+}
+
+template <class K>
+static float time_kernel(K kern, const uint16_t *A, const uint16_t *B, int Mi, int Nj, int Kl, int planes, float *sink, int grid,
+                         int iters)
+{
+    const int smem = 131072;
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return -1.f;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return -1.f;
+    for (int i = 0; i < 3; ++i) hipLaunchKernelGGL(kern, dim3(grid), dim3(512), smem, 0, A, B, Mi, Nj, Kl, planes, sink);
+    (void)hipEventRecord(e0, 0);
+    for (int i = 0; i < iters; ++i) hipLaunchKernelGGL(kern, dim3(grid), dim3(512), smem, 0, A, B, Mi, Nj, Kl, planes, sink);
+    (void)hipEventRecord(e1, 0);
+    if (hipEventSynchronize(e1) != hipSuccess) return -1.f;
+    float ms = 0.f;
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return ms / iters;
+}
+
 template <int MODE>
 static float run(const uint16_t *A, const uint16_t *B, int Mi, int Nj, int Kl, int planes, float *sink, int grid, int iters)
 {
@@ -135,5 +239,41 @@ extern "C" float stl_probe_run(int mode, const void *A, const void *B, int Mi, i
         case 5: return run<5>(a, b, Mi, Nj, Kl, planes, s, grid, iters);
         case 7: return run<7>(a, b, Mi, Nj, Kl, planes, s, grid, iters);
     }
+    return -2.f;
+}
+
+// Depth form.  id = 100 * placement + depth: placement 0 = loads in front of the stage's MFMAs, 1 = spread between them,
+// 2 = spread and a barrier per stage; depth (instructions in flight at the end of a stage) one of 4, 8, 16, 32, 48 for
+// placement 0 and 4, 8, 16, 32 for the others; id 1000 + depth (8, 16, 32) = loads only; id 2000 / 2001 = MFMAs only
+// without / with the barrier.  Same arguments and return value as stl_probe_run.
+extern "C" float stl_probe_depth_run(int id, const void *A, const void *B, int Mi, int Nj, int Kl, int planes, void *sink, int grid,
+                                     int iters)
+{
+    if (Mi % 256 || Nj % 256 || Kl % 64 || planes < 1 || grid < 1 || iters < 1) return -2.f;
+    const uint16_t *a = (const uint16_t *)A, *b = (const uint16_t *)B;
+    float *s = (float *)sink;
+#define STL_PROBE_CASE(ID, M, D, S, Bb) \
+    case ID: return time_kernel(probe_depth_kernel<M, D, S, Bb>, a, b, Mi, Nj, Kl, planes, s, grid, iters);
+    switch (id) {
+        STL_PROBE_CASE(2000, 2, 0, 0, 0)
+        STL_PROBE_CASE(2001, 2, 0, 0, 1)
+        STL_PROBE_CASE(1008, 1, 8, 0, 0)
+        STL_PROBE_CASE(1016, 1, 16, 0, 0)
+        STL_PROBE_CASE(1032, 1, 32, 0, 0)
+        STL_PROBE_CASE(4, 3, 4, 0, 0)
+        STL_PROBE_CASE(8, 3, 8, 0, 0)
+        STL_PROBE_CASE(16, 3, 16, 0, 0)
+        STL_PROBE_CASE(32, 3, 32, 0, 0)
+        STL_PROBE_CASE(48, 3, 48, 0, 0)
+        STL_PROBE_CASE(104, 3, 4, 1, 0)
+        STL_PROBE_CASE(108, 3, 8, 1, 0)
+        STL_PROBE_CASE(116, 3, 16, 1, 0)
+        STL_PROBE_CASE(132, 3, 32, 1, 0)
+        STL_PROBE_CASE(204, 3, 4, 1, 1)
+        STL_PROBE_CASE(208, 3, 8, 1, 1)
+        STL_PROBE_CASE(216, 3, 16, 1, 1)
+        STL_PROBE_CASE(232, 3, 32, 1, 1)
+    }
+#undef STL_PROBE_CASE
     return -2.f;
 }

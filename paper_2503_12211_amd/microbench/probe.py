@@ -1,7 +1,7 @@
 """Runs the L2->LDS / MFMA probe (dma_mfma_probe.hip) at the benchmark shape of the plane products and prints a small
 table.  Measurement aid for the figures about what bounds the plane-product kernel; not part of the library.
 
-    python -m paper_2503_12211_amd.microbench.probe            (builds the probe next to this file if needed)
+    python -m paper_2503_12211_amd.microbench.probe [--depth]  (builds the probe next to this file if needed)
 """
 from __future__ import annotations
 
@@ -22,6 +22,23 @@ def build() -> Path:
     if res.returncode != 0:
         raise RuntimeError(res.stderr)
     return LIB
+
+
+def depth_table(lib, A, B, sink, Mi, Nj, Kl, r, cus):
+    """Whole-line loads with the prefetch depth, the placement of the loads and a barrier per stage varied."""
+    lib.stl_probe_depth_run.restype = ctypes.c_float
+    lib.stl_probe_depth_run.argtypes = lib.stl_probe_run.argtypes
+    rows = [(2000, "MFMA only"), (2001, "MFMA only, barrier per stage")]
+    rows += [(1000 + d, f"loads only, {d} in flight") for d in (8, 16, 32)]
+    rows += [(d, f"loads in front of the MFMAs, {d} in flight") for d in (4, 8, 16, 32, 48)]
+    rows += [(100 + d, f"loads between the MFMAs, {d} in flight") for d in (4, 8, 16, 32)]
+    rows += [(200 + d, f"between + barrier per stage, {d} in flight") for d in (4, 8, 16, 32)]
+    print("depth form (whole-line loads; load instructions a wavefront may leave in flight at the end of a stage):")
+    for ident, name in rows:
+        ms = lib.stl_probe_depth_run(ident, A.data_ptr(), B.data_ptr(), Mi, Nj, Kl, r, sink.data_ptr(), cus, 20)
+        if ms < 0:
+            raise RuntimeError(f"probe {ident} failed ({ms})")
+        print(f"  {name:46s} {ms * 1e3:8.1f} us", flush=True)
 
 
 def main():
@@ -56,6 +73,8 @@ def main():
         if mode & 2:
             line += f"   {flop / ms / 1e9:7.1f} TFLOP/s"
         print(line, flush=True)
+    if "--depth" in sys.argv:
+        depth_table(lib, A, B, sink, Mi, Nj, Kl, r, cus)
 
 
 if __name__ == "__main__":

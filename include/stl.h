@@ -86,7 +86,8 @@ enum {
     STL_FLAG_FUSED = 3,     /* one launch: encode -> MFMA -> decode, no plane ever written to HBM   */
     STL_FLAG_PIPELINED = 4, /* one persistent launch over the three-launch kernels' own code: encode and decode items of
                                neighbouring row blocks run on some CUs while others multiply; same planes in HBM and
-                               bit-identical results; bf16, r <= 32, k and n multiples of 256, m >= 2048 (else UNSUPPORTED) */
+                               bit-identical results; bf16, r <= 32, k and n multiples of 256, n >= 1024,
+                               2048 <= m <= 4194304 (else UNSUPPORTED) */
     STL_FLAG_VARIANT_MASK = 0xff,
     STL_FLAG_GELU = 0x100,  /* C <- gelu(C) (exact erf form) applied in fp32 before the final rounding */
     STL_FLAG_B_TRANSPOSED = 0x200   /* stl_aa_*: the second operand is stored transposed, (nbatch*n) x k */

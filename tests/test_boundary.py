@@ -94,6 +94,18 @@ def test_block_resident_variants_reject_unsupported_shapes():
     assert stl.stl_workspace_bytes(prob, stl.STL_OP_FORWARD, stl.STL_FLAG_FUSED) == 0
 
 
+def test_pipelined_variant_rejects_what_the_header_excludes():
+    """STL_FLAG_PIPELINED: bf16, r <= 32, k and n multiples of 256, n >= 1024, m >= 2048 -- anything else is refused before
+    any launch (the pointers here are not device memory)."""
+    ok = dict(m=2048, k=1024, n=1024, r=32, dtype=stl.STL_BF16)
+    assert stl.stl_workspace_bytes(stl.Problem(**ok), stl.STL_OP_FORWARD, stl.STL_FLAG_PIPELINED) > 0
+    for kw in (dict(r=33), dict(k=1024 + 128), dict(n=1024 + 64), dict(n=768), dict(m=2044), dict(m=1024), dict(dtype=stl.STL_F32)):
+        prob = stl.Problem(**{**ok, **kw})
+        with pytest.raises(stl.StlError) as e:
+            stl.stl_forward(prob, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 1 << 40, stl.STL_FLAG_PIPELINED, stream=0)
+        assert e.value.status == 2, kw
+
+
 def test_layer_pair_argument_checks():
     """stl_mlp_forward / stl_recode: chaining, variant, pointer and workspace checks happen before any launch."""
     up = stl.Problem(512, 256, 1024, 24, stl.STL_BF16)

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_pipe_kernel(const 
     extern __shared__ __align__(16) char smem[];
     char *slab = smem + NS * STAGE_BYTES + (threadIdx.x >> 6) * SLAB;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: LDS-DMA destinations stay in SGPRs
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int per_plane = tiles_m * tiles_n;
     const int nks = Kl / BKS;

@@ -25,7 +25,7 @@ __global__ __launch_bounds__(512) void gemm_pipe_wide_kernel(const bf16_t *__res
     constexpr int RP = 16, PITCH = WN * 2 + 16, SLAB = RP * PITCH;
     static_assert(B_BASE + NSB * B_STAGE == 160 * 1024 && NW * SLAB <= A_SLOT, "LDS map");
     extern __shared__ __align__(16) char smem[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: LDS-DMA destinations stay in SGPRs
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     char *slab = smem + 2 * A_SLOT + wave * SLAB;
     const int per_plane = tiles_m * tiles_n;

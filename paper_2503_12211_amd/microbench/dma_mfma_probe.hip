@@ -101,7 +101,8 @@ __global__ __launch_bounds__(512) void probe_kernel(const uint16_t *__restrict__
 
 // Second form of the probe: whole-line loads only, with the number of load instructions a wavefront may leave in flight
 // at the end of a stage (DEPTH, four instructions per stage), the placement of the loads (SPREAD: one after every fourth
-// MFMA instead of all four in front of the stage's MFMAs) and a workgroup barrier per stage (BAR) as parameters.
+// MFMA instead of all four in front of the stage's MFMAs; 2, 3: the same with the wavefronts staggered) and a workgroup
+// barrier per stage (BAR) as parameters.
 template <int MODE, int DEPTH, int SPREAD, int BAR>
 __global__ __launch_bounds__(512) void probe_depth_kernel(const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int Mi,
                                                           int Nj, int Kl, int planes, float *__restrict__ sink)
@@ -112,6 +113,10 @@ __global__ __launch_bounds__(512) void probe_depth_kernel(const uint16_t *__rest
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int tiles_m = Mi / 256, tiles_n = Nj / 256, per_plane = tiles_m * tiles_n, total = per_plane * planes;
     const int nks = Kl / 32;
+    // MFMA (of every four) after which this wavefront issues a load: the same for all (SPREAD 1), or staggered so that the
+    // eight wavefronts of the workgroup never issue theirs together (2: by wavefront pair, 3: by wavefront index mod 4)
+    const int issue_after = SPREAD == 2 ? __builtin_amdgcn_readfirstlane((wave >> 1) & 3)
+                          : SPREAD == 3 ? __builtin_amdgcn_readfirstlane(wave & 3) : 1;
     f32x16_t acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -160,7 +165,7 @@ __global__ __launch_bounds__(512) void probe_depth_kernel(const uint16_t *__rest
                         acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[i & 1], va[i >> 1], acc[i], 0, 0, 0);
                         if (SPREAD) {
                             __builtin_amdgcn_sched_barrier(0);
-                            if (DMA && (i & 3) == 1) {
+                            if (DMA && (i & 3) == issue_after) {
                                 dma16(src[ks * 2 + (i >> 2)], dst[ks * 2 + (i >> 2)]);
                                 __builtin_amdgcn_sched_barrier(0);
                             }
@@ -243,7 +248,8 @@ extern "C" float stl_probe_run(int mode, const void *A, const void *B, int Mi, i
 }
 
 // Depth form.  id = 100 * placement + depth: placement 0 = loads in front of the stage's MFMAs, 1 = spread between them,
-// 2 = spread and a barrier per stage; depth (instructions in flight at the end of a stage) one of 4, 8, 16, 32, 48 for
+// 2 = spread and a barrier per stage, 3 / 4 = staggered by wavefront pair without / with the barrier, 5 / 6 = staggered by
+// wavefront index mod 4 (depth 8 only); depth (instructions in flight at the end of a stage) one of 4, 8, 16, 32, 48 for
 // placement 0 and 4, 8, 16, 32 for the others; id 1000 + depth (8, 16, 32) = loads only; id 2000 / 2001 = MFMAs only
 // without / with the barrier.  Same arguments and return value as stl_probe_run.
 extern "C" float stl_probe_depth_run(int id, const void *A, const void *B, int Mi, int Nj, int Kl, int planes, void *sink, int grid,
@@ -273,6 +279,10 @@ extern "C" float stl_probe_depth_run(int id, const void *A, const void *B, int M
         STL_PROBE_CASE(208, 3, 8, 1, 1)
         STL_PROBE_CASE(216, 3, 16, 1, 1)
         STL_PROBE_CASE(232, 3, 32, 1, 1)
+        STL_PROBE_CASE(308, 3, 8, 2, 0)
+        STL_PROBE_CASE(408, 3, 8, 2, 1)
+        STL_PROBE_CASE(508, 3, 8, 3, 0)
+        STL_PROBE_CASE(608, 3, 8, 3, 1)
     }
 #undef STL_PROBE_CASE
     return -2.f;

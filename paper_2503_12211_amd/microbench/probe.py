@@ -33,6 +33,8 @@ def depth_table(lib, A, B, sink, Mi, Nj, Kl, r, cus):
     rows += [(d, f"loads in front of the MFMAs, {d} in flight") for d in (4, 8, 16, 32, 48)]
     rows += [(100 + d, f"loads between the MFMAs, {d} in flight") for d in (4, 8, 16, 32)]
     rows += [(200 + d, f"between + barrier per stage, {d} in flight") for d in (4, 8, 16, 32)]
+    rows += [(308, "staggered by wavefront pair, 8 in flight"), (408, "the same + barrier per stage"),
+             (508, "staggered by wavefront index mod 4, 8 in flight"), (608, "the same + barrier per stage")]
     print("depth form (whole-line loads; load instructions a wavefront may leave in flight at the end of a stage):")
     for ident, name in rows:
         ms = lib.stl_probe_depth_run(ident, A.data_ptr(), B.data_ptr(), Mi, Nj, Kl, r, sink.data_ptr(), cus, 20)

@@ -115,6 +115,9 @@ __global__ __launch_bounds__(512) void probe_depth_kernel(const uint16_t *__rest
     const int nks = Kl / 32;
     // MFMA (of every four) after which this wavefront issues a load: the same for all (SPREAD 1), or staggered so that the
     // eight wavefronts of the workgroup never issue theirs together (2: by wavefront pair, 3: by wavefront index mod 4)
+    // pair forms: wavefronts w and w + 4 (SPREAD 4) or 2i and 2i + 1 (SPREAD 5); the first of a pair issues all eight loads
+    const int partner = __builtin_amdgcn_readfirstlane(SPREAD == 4 ? (wave ^ 4) : (wave ^ 1));
+    const bool loader = SPREAD == 4 ? __builtin_amdgcn_readfirstlane(wave) < 4 : (__builtin_amdgcn_readfirstlane(wave) & 1) == 0;
     const int issue_after = SPREAD == 2 ? __builtin_amdgcn_readfirstlane((wave >> 1) & 3)
                           : SPREAD == 3 ? __builtin_amdgcn_readfirstlane(wave & 3) : 1;
     f32x16_t acc[8];
@@ -139,19 +142,25 @@ __global__ __launch_bounds__(512) void probe_depth_kernel(const uint16_t *__rest
         const int i0 = (rem / tiles_n) * 256, j0 = (rem % tiles_n) * 256;
         const uint16_t *Ap = A + (size_t)p * Mi * Kl, *Bp = B + (size_t)p * Kl * Nj;
         for (int s = 0; s < nks; ++s) {
-            const uint16_t *src[4];
-            uint32_t dst[4];
+            // the four loads of wavefront index w (entries 4h .. 4h+3): this wavefront's own (h = 0) and, where one wavefront
+            // of a pair issues for both (SPREAD 4, 5), its partner's (h = 1)
+            const uint16_t *src[8];
+            uint32_t dst[8];
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {   // whole lines of the [row][l] operand
-                const int q = 16 * (s & 1) + 2 * wave + j, row = 8 * q + (lane >> 3), c = lane & 7;
-                src[j] = Ap + (size_t)(i0 + row) * Kl + (s & ~1) * 32 + 8 * c;
-                dst[j] = lds0 + (uint32_t)((s >> 1) & 1) * 32768u + q * 1024;
-            }
+            for (int h = 0; h < 2; ++h) {
+                const int w = h == 0 ? wave : partner;
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int q = 2 * wave + j, k = 2 * q + (lane >> 5), nc = lane & 31;
-                src[2 + j] = Bp + (size_t)(s * 32 + k) * Nj + j0 + 8 * nc;
-                dst[2 + j] = lds0 + 65536u + (uint32_t)(s & 3) * 16384u + q * 1024;
+                for (int j = 0; j < 2; ++j) {   // whole lines of the [row][l] operand
+                    const int q = 16 * (s & 1) + 2 * w + j, row = 8 * q + (lane >> 3), c = lane & 7;
+                    src[4 * h + j] = Ap + (size_t)(i0 + row) * Kl + (s & ~1) * 32 + 8 * c;
+                    dst[4 * h + j] = lds0 + (uint32_t)((s >> 1) & 1) * 32768u + q * 1024;
+                }
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int q = 2 * w + j, k = 2 * q + (lane >> 5), nc = lane & 31;
+                    src[4 * h + 2 + j] = Bp + (size_t)(s * 32 + k) * Nj + j0 + 8 * nc;
+                    dst[4 * h + 2 + j] = lds0 + 65536u + (uint32_t)(s & 3) * 16384u + q * 1024;
+                }
             }
             if (DMA && !SPREAD) {
 #pragma unroll
@@ -163,7 +172,13 @@ __global__ __launch_bounds__(512) void probe_depth_kernel(const uint16_t *__rest
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[i & 1], va[i >> 1], acc[i], 0, 0, 0);
-                        if (SPREAD) {
+                        if (SPREAD >= 4) {              // one wavefront of each pair issues the loads of both
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (DMA && (i & 1) == 1 && loader) {
+                                dma16(src[ks * 4 + (i >> 1)], dst[ks * 4 + (i >> 1)]);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        } else if (SPREAD) {
                             __builtin_amdgcn_sched_barrier(0);
                             if (DMA && (i & 3) == issue_after) {
                                 dma16(src[ks * 2 + (i >> 2)], dst[ks * 2 + (i >> 2)]);
@@ -175,6 +190,7 @@ __global__ __launch_bounds__(512) void probe_depth_kernel(const uint16_t *__rest
 #pragma unroll
                 for (int j = 0; j < 4; ++j) dma16(src[j], dst[j]);
             }
+            static_assert(!(SPREAD >= 4) || (MODE == 3), "the pair forms exist for loads + MFMA only");
             if (DMA) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DEPTH) : "memory");
             if (BAR) asm volatile("s_barrier" ::: "memory");
         }
@@ -249,7 +265,8 @@ extern "C" float stl_probe_run(int mode, const void *A, const void *B, int Mi, i
 
 // Depth form.  id = 100 * placement + depth: placement 0 = loads in front of the stage's MFMAs, 1 = spread between them,
 // 2 = spread and a barrier per stage, 3 / 4 = staggered by wavefront pair without / with the barrier, 5 / 6 = staggered by
-// wavefront index mod 4 (depth 8 only); depth (instructions in flight at the end of a stage) one of 4, 8, 16, 32, 48 for
+// wavefront index mod 4 (depth 8 only), 7 / 8 = wavefronts w < 4 issue the loads of w and w + 4 without / with the barrier,
+// 9 / 11 = even wavefronts issue the loads of 2i and 2i + 1 (depth 16 only: eight loads per stage and loading wavefront); depth (instructions in flight at the end of a stage) one of 4, 8, 16, 32, 48 for
 // placement 0 and 4, 8, 16, 32 for the others; id 1000 + depth (8, 16, 32) = loads only; id 2000 / 2001 = MFMAs only
 // without / with the barrier.  Same arguments and return value as stl_probe_run.
 extern "C" float stl_probe_depth_run(int id, const void *A, const void *B, int Mi, int Nj, int Kl, int planes, void *sink, int grid,
@@ -283,6 +300,10 @@ extern "C" float stl_probe_depth_run(int id, const void *A, const void *B, int M
         STL_PROBE_CASE(408, 3, 8, 2, 1)
         STL_PROBE_CASE(508, 3, 8, 3, 0)
         STL_PROBE_CASE(608, 3, 8, 3, 1)
+        STL_PROBE_CASE(716, 3, 16, 4, 0)
+        STL_PROBE_CASE(816, 3, 16, 4, 1)
+        STL_PROBE_CASE(916, 3, 16, 5, 0)
+        STL_PROBE_CASE(1116, 3, 16, 5, 1)
     }
 #undef STL_PROBE_CASE
     return -2.f;

@@ -107,7 +107,7 @@ template <int MODE, int DEPTH, int SPREAD, int BAR>
 __global__ __launch_bounds__(512) void probe_depth_kernel(const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int Mi,
                                                           int Nj, int Kl, int planes, float *__restrict__ sink)
 {
-    constexpr bool DMA = MODE & 1, MFMA = MODE & 2;
+    constexpr bool DMA = MODE & 1, MFMA = MODE & 2, ZERO = MODE & 8;   // ZERO: all-zero MFMA operands (least switching)
     extern __shared__ __align__(16) char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char *)smem);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -129,11 +129,11 @@ __global__ __launch_bounds__(512) void probe_depth_kernel(const uint16_t *__rest
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) va[i][e] = (__bf16)(0.01f * (lane + i + e));
+        for (int e = 0; e < 8; ++e) va[i][e] = ZERO ? (__bf16)0.f : (__bf16)(0.01f * (lane + i + e));
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) vb[i][e] = (__bf16)(0.02f * (lane - i - e));
+        for (int e = 0; e < 8; ++e) vb[i][e] = ZERO ? (__bf16)0.f : (__bf16)(0.02f * (lane - i - e));
 
     for (int v = blockIdx.x; v < total; v += gridDim.x) {
         int lid = v;
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(512) void probe_depth_kernel(const uint16_t *__rest
 #pragma unroll
                 for (int j = 0; j < 4; ++j) dma16(src[j], dst[j]);
             }
-            static_assert(!(SPREAD >= 4) || (MODE == 3), "the pair forms exist for loads + MFMA only");
+            static_assert(!(SPREAD >= 4) || ((MODE & 3) == 3), "the pair forms exist for loads + MFMA only");
             if (DMA) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DEPTH) : "memory");
             if (BAR) asm volatile("s_barrier" ::: "memory");
         }
@@ -266,7 +266,8 @@ extern "C" float stl_probe_run(int mode, const void *A, const void *B, int Mi, i
 // Depth form.  id = 100 * placement + depth: placement 0 = loads in front of the stage's MFMAs, 1 = spread between them,
 // 2 = spread and a barrier per stage, 3 / 4 = staggered by wavefront pair without / with the barrier, 5 / 6 = staggered by
 // wavefront index mod 4 (depth 8 only), 7 / 8 = wavefronts w < 4 issue the loads of w and w + 4 without / with the barrier,
-// 9 / 11 = even wavefronts issue the loads of 2i and 2i + 1 (depth 16 only: eight loads per stage and loading wavefront); depth (instructions in flight at the end of a stage) one of 4, 8, 16, 32, 48 for
+// 9 / 11 = even wavefronts issue the loads of 2i and 2i + 1 (depth 16 only: eight loads per stage and loading wavefront);
+// id 3000 / 3008 = MFMAs only / loads between the MFMAs with all-zero MFMA operands; depth (instructions in flight at the end of a stage) one of 4, 8, 16, 32, 48 for
 // placement 0 and 4, 8, 16, 32 for the others; id 1000 + depth (8, 16, 32) = loads only; id 2000 / 2001 = MFMAs only
 // without / with the barrier.  Same arguments and return value as stl_probe_run.
 extern "C" float stl_probe_depth_run(int id, const void *A, const void *B, int Mi, int Nj, int Kl, int planes, void *sink, int grid,
@@ -304,6 +305,8 @@ extern "C" float stl_probe_depth_run(int id, const void *A, const void *B, int M
         STL_PROBE_CASE(816, 3, 16, 4, 1)
         STL_PROBE_CASE(916, 3, 16, 5, 0)
         STL_PROBE_CASE(1116, 3, 16, 5, 1)
+        STL_PROBE_CASE(3000, 10, 0, 0, 0)
+        STL_PROBE_CASE(3008, 11, 8, 1, 0)
     }
 #undef STL_PROBE_CASE
     return -2.f;

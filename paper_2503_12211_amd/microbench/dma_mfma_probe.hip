@@ -12,6 +12,7 @@
 #include <hip/hip_runtime.h>
 #include <cstdint>
 #include <cstdio>
+#include <type_traits>
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
@@ -204,6 +205,68 @@ __global__ __launch_bounds__(512) void probe_depth_kernel(const uint16_t *__rest
     if (t == 12345.678f) sink[threadIdx.x] = t;     // keeps the products alive; never true
 }
 
+// Third form: no LDS at all for the first operand.  Every wavefront owns 32 rows of the block and loads its own MFMA
+// fragments of that operand straight from memory into registers (lane = (row, half of the 16-element step): 16 bytes),
+// RING steps ahead, with ordinary loads the compiler tracks; the second operand stays in registers.  Measures what
+// register-returning loads cost the matrix cores, against the LDS-DMA loads of the other forms.  The contraction length
+// is fixed (1024 elements = 64 steps, unrolled) so that every ring index and every "is there a next step" is a constant.
+template <int I, int N, class F>
+__device__ __forceinline__ void probe_static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        probe_static_for<I + 1, N>(f);
+    }
+}
+
+template <int RING>
+__global__ __launch_bounds__(512) void probe_direct_kernel(const uint16_t *__restrict__ A, const uint16_t *__restrict__ B, int Mi,
+                                                           int Nj, int Kl, int planes, float *__restrict__ sink)
+{
+    (void)B;
+    constexpr int STEPS = 64;                               // Kl == 1024, checked by the caller
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tiles_m = Mi / 256, tiles_n = Nj / 256, per_plane = tiles_m * tiles_n, total = per_plane * planes;
+    f32x16_t acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    bf16x8_t vb[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vb[i][e] = (__bf16)(0.02f * (lane - i - e));
+
+    for (int v = blockIdx.x; v < total; v += gridDim.x) {
+        int lid = v;
+        if ((total & 7) == 0 && (gridDim.x & 7) == 0) lid = (v & 7) * (total >> 3) + (v >> 3);
+        const int p = lid / per_plane, rem = lid - p * per_plane;
+        const int i0 = (rem / tiles_n) * 256;
+        // this lane's row of the block and its half of every 16-element step: 16-byte pieces at rowp + 16 * step
+        const uint16_t *rowp = A + (size_t)p * Mi * Kl + (size_t)(i0 + 32 * wave + (lane & 31)) * Kl + 8 * (lane >> 5);
+        bf16x8_t ring[RING];
+#pragma unroll
+        for (int d = 0; d < RING; ++d) ring[d] = *reinterpret_cast<const bf16x8_t *>(rowp + 16 * d);
+        __builtin_amdgcn_sched_barrier(0);
+        probe_static_for<0, STEPS>([&](auto t_c) {
+            constexpr int t = decltype(t_c)::value, d = t % RING;
+            const bf16x8_t va = ring[d];
+            if constexpr (t + RING < STEPS) ring[d] = *reinterpret_cast<const bf16x8_t *>(rowp + 16 * (t + RING));
+            __builtin_amdgcn_sched_barrier(0);              // the load stays RING steps ahead of its use
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[i & 1], va, acc[i], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) t += acc[i][e];
+    if (t == 12345.678f) sink[threadIdx.x] = t;     // keeps the products alive; never true
+}
+
 template <class K>
 static float time_kernel(K kern, const uint16_t *A, const uint16_t *B, int Mi, int Nj, int Kl, int planes, float *sink, int grid,
                          int iters)
@@ -267,7 +330,8 @@ extern "C" float stl_probe_run(int mode, const void *A, const void *B, int Mi, i
 // 2 = spread and a barrier per stage, 3 / 4 = staggered by wavefront pair without / with the barrier, 5 / 6 = staggered by
 // wavefront index mod 4 (depth 8 only), 7 / 8 = wavefronts w < 4 issue the loads of w and w + 4 without / with the barrier,
 // 9 / 11 = even wavefronts issue the loads of 2i and 2i + 1 (depth 16 only: eight loads per stage and loading wavefront);
-// id 3000 / 3008 = MFMAs only / loads between the MFMAs with all-zero MFMA operands; depth (instructions in flight at the end of a stage) one of 4, 8, 16, 32, 48 for
+// id 3000 / 3008 = MFMAs only / loads between the MFMAs with all-zero MFMA operands; id 4004 / 4008 = the direct form with
+// 4 / 8 steps of register prefetch (Kl = 1024 only); depth (instructions in flight at the end of a stage) one of 4, 8, 16, 32, 48 for
 // placement 0 and 4, 8, 16, 32 for the others; id 1000 + depth (8, 16, 32) = loads only; id 2000 / 2001 = MFMAs only
 // without / with the barrier.  Same arguments and return value as stl_probe_run.
 extern "C" float stl_probe_depth_run(int id, const void *A, const void *B, int Mi, int Nj, int Kl, int planes, void *sink, int grid,
@@ -307,6 +371,8 @@ extern "C" float stl_probe_depth_run(int id, const void *A, const void *B, int M
         STL_PROBE_CASE(1116, 3, 16, 5, 1)
         STL_PROBE_CASE(3000, 10, 0, 0, 0)
         STL_PROBE_CASE(3008, 11, 8, 1, 0)
+        case 4004: if (Kl != 1024) return -2.f; return time_kernel(probe_direct_kernel<4>, a, b, Mi, Nj, Kl, planes, s, grid, iters);
+        case 4008: if (Kl != 1024) return -2.f; return time_kernel(probe_direct_kernel<8>, a, b, Mi, Nj, Kl, planes, s, grid, iters);
     }
 #undef STL_PROBE_CASE
     return -2.f;

@@ -38,6 +38,7 @@ def depth_table(lib, A, B, sink, Mi, Nj, Kl, r, cus):
     rows += [(716, "wavefronts 0-3 load for w and w + 4"), (816, "the same + barrier per stage"),
              (916, "even wavefronts load for 2i and 2i + 1"), (1116, "the same + barrier per stage")]
     rows += [(3000, "MFMA only, all-zero operands"), (3008, "loads between the MFMAs, all-zero operands")]
+    rows += [(4004, "first operand straight into registers, 4 ahead"), (4008, "the same, 8 steps ahead")]
     print("depth form (whole-line loads; load instructions a wavefront may leave in flight at the end of a stage):")
     for ident, name in rows:
         ms = lib.stl_probe_depth_run(ident, A.data_ptr(), B.data_ptr(), Mi, Nj, Kl, r, sink.data_ptr(), cus, 20)

@@ -32,10 +32,10 @@
 // Measured (bf16, m = 8192, k = n = 4096): this launch takes 0.25 ms at r = 32 and 0.17 ms at r = 8, the three separate
 // launches 0.215 and 0.075 ms.  With every wait switched off (wrong results, timing only) it takes 0.208 and 0.086 ms,
 // with the tile maps skipped as well 0.154 and 0.053 ms: the tile-map items cost as much wall time between the product
-// blocks as they cost on their own.  The chip runs the plane products at its power limit (1.7-1.9 GHz instead of
-// 2.4), and what the streaming items draw comes out of the same budget, so overlapping the HBM-bound and the
-// matrix-core-bound work of this operator gains nothing on this GPU; the waits of the real list cost another
-// 0.04-0.08 ms.  The variant is therefore selectable (STL_FLAG_PIPELINED) but never chosen automatically.
+// blocks as they cost on their own.  A CU that runs a tile-map item does not multiply meanwhile (one workgroup per CU:
+// the product code needs the whole LDS), and the items take nearly their stand-alone time although the other CUs leave
+// most of the HBM bandwidth unused, so overlapping the HBM-bound and the matrix-core-bound work of this operator gains
+// nothing on this GPU; the waits of the real list cost another 0.04-0.08 ms.  The variant is therefore selectable (STL_FLAG_PIPELINED) but never chosen automatically.
 //
 // Arithmetic, rounding and summation order are exactly those of the three separate kernels (same device functions,
 // same block code): the results are bit-identical to the three-launch path.
